@@ -1,0 +1,268 @@
+"""Pins for oracle/occult_ref.py and oracle/moe_std.py: exactness of the deduplicated path,
+once-per-device dispatch, replica bounds, the paper's worked example, a closed form for
+uniform routing, library reductions and brute force on tiny inputs."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from inputs import workloads as wl
+from oracle import moe_std, occult_ref, routing
+
+
+def _parse_golden(path):
+    out = {}
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, rest = line.split(" ", 1)
+        out[key] = rest
+    return out
+
+
+def _mat(s):
+    return np.array([[int(v) for v in row.split()] for row in s.split("/")])
+
+
+# ---------------------------------------------------------------- worked example (Figure 2)
+def test_fig2_instance_traces_and_replica_counts(golden_dir):
+    g = _parse_golden(f"{golden_dir}/fig2_instance.txt")
+    fig = _parse_golden(f"{golden_dir}/fig2_workflows.txt")
+    ids = _mat(g["ids"]).astype(np.int32)
+    w = np.full(ids.shape, 0.5)
+    x = np.arange(4 * 3, dtype=np.float64).reshape(4, 3)
+    pos = wl.contiguous_placement(4, 2)
+    tr = occult_ref.moe_forward(x, ids, w, pos, D=2)
+    assert np.array_equal(tr.brim_0, _mat(g["brim0"]))
+    assert np.array_equal(tr.brim_1[0], _mat(g["brim1_dev0"]))
+    assert np.array_equal(tr.brim_1[1], _mat(g["brim1_dev1"]))
+    assert tr.dev_count.tolist() == [int(v) for v in g["dev_count"].split()]
+    assert tr.n_sfd == int(g["n_sfd"]) and tr.n_epd == int(g["n_epd"])
+    sfd_token = [int(v) for v in g["sfd_token"].split()]
+    assert np.array_equal(tr.x_sfd, x[sfd_token])
+    # panel (b): deduplicated dispatch
+    assert tr.c_t == float(fig["occult"])
+    # panel (a): classical dispatch = every expert its own device
+    tr_std = occult_ref.moe_forward(x, ids, w, np.arange(4, dtype=np.int32), D=4)
+    assert tr_std.c_t == float(fig["classical"])
+    # panel (c): pruning to one device; router scores that reproduce ids as plain top-2
+    lg = np.full((4, 4), -5.0, dtype=np.float32)
+    for t in range(4):
+        lg[t, ids[t, 0]] = 2.0
+        lg[t, ids[t, 1]] = 1.0
+    ids_chk, _ = routing.route(lg, 2, 2, pos)
+    assert np.array_equal(ids_chk, ids)
+    for mode in (1, 2):
+        ids_p, w_p = routing.route(lg, 2, 2, pos, n_d=1, prune_mode=mode)
+        tr_p = occult_ref.moe_forward(x, ids_p, w_p, pos, D=2)
+        assert tr_p.c_t == float(fig["occult_pruned"])
+
+
+# ---------------------------------------------------------------- loops vs running counts
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_brim_builders_equal_printed_loops(seed):
+    E, D, k, T = 12, 3, 4, 97
+    lg = wl.random_logits(T, E, seed=seed, ties=True)
+    pos = wl.random_placement(E, D, seed=seed + 10)
+    ids, w = routing.route(lg, k, D, pos)
+    L = occult_ref.placement_lists(pos, D)
+    b0 = occult_ref.build_brim_0(ids, L)
+    assert np.array_equal(b0, occult_ref.build_brim_0_loops(ids, L))
+    x = np.random.default_rng(seed).standard_normal((T, 8))
+    xs, ids_s, w_s = occult_ref.dispatch(x, ids, w, b0)
+    cnt = (b0 >= 0).sum(axis=1)
+    off = np.concatenate([[0], np.cumsum(cnt)])
+    for j in range(D):
+        seg = slice(off[j], off[j + 1])
+        a = occult_ref.build_brim_1(ids_s[seg], w_s[seg], L[j])
+        b = occult_ref.build_brim_1_loops(ids_s[seg], w_s[seg], L[j])
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+# ---------------------------------------------------------------- once per device, bounds
+def _check_once_per_device(ids, pos, D, tr):
+    T, k = ids.shape
+    E = len(pos)
+    G = E // D
+    dev = np.asarray(pos)[ids] // G
+    n = 0
+    for t in range(T):
+        devset = set(dev[t].tolist())
+        for j in range(D):
+            assert (tr.brim_0[j, t] >= 0) == (j in devset)
+        assert math.ceil(k / G) <= len(devset) <= min(k, D)       # replica bounds, Section 2.2
+        n += len(devset)
+    assert tr.n_sfd == n
+    flat = tr.brim_0[tr.brim_0 >= 0]
+    assert sorted(flat.tolist()) == list(range(n))                 # rows are a permutation
+    for j in range(D):                                             # token-ascending per device
+        v = tr.brim_0[j][tr.brim_0[j] >= 0]
+        assert np.all(np.diff(v) == 1)
+    assert tr.n_epd == T * k
+
+
+@pytest.mark.parametrize("E,D,k", [(16, 4, 4), (60, 4, 4), (64, 8, 8), (64, 16, 6), (8, 8, 2)])
+def test_each_token_once_per_distinct_device_and_bounds(E, D, k):
+    T = 300
+    lg = wl.random_logits(T, E, seed=E + D + k)
+    for pos in (wl.contiguous_placement(E, D), wl.random_placement(E, D, seed=5)):
+        ids, w = routing.route(lg, k, D, pos)
+        tr = occult_ref.moe_forward(np.zeros((T, 2)), ids, w, pos, D)
+        _check_once_per_device(ids, pos, D, tr)
+        lo, hi = math.ceil(k * D / E), min(k, D)
+        assert lo <= tr.c_t <= hi
+
+
+def test_stable_sort_reproduces_sfd_and_epd_order():
+    # SFD order = stable sort of (token, device) pairs by device; EPD order under contiguous
+    # placement = stable sort of (token, expert) pairs by expert
+    E, D, k, T = 32, 4, 4, 500
+    G = E // D
+    lg = wl.random_logits(T, E, seed=77)
+    pos = wl.contiguous_placement(E, D)
+    ids, w = routing.route(lg, k, D, pos)
+    x = np.arange(T, dtype=np.float64)[:, None] * np.ones((1, 2))
+    tr = occult_ref.moe_forward(x, ids, w, pos, D)
+    pairs = sorted({(int(e) // G, t) for t in range(T) for e in ids[t]})
+    assert [t for _, t in pairs] == tr.x_sfd[:, 0].astype(int).tolist()
+    tok = np.repeat(np.arange(T), k)
+    order = np.argsort(ids.reshape(-1), kind="stable")
+    # expand BRIM_1 to (global EPD row -> token)
+    cnt = tr.dev_count
+    off = np.concatenate([[0], np.cumsum(cnt)])
+    epd_tok, base = {}, 0
+    sfd_tok = tr.x_sfd[:, 0].astype(int)
+    for j in range(D):
+        b1 = tr.brim_1[j]
+        for e in range(G):
+            for s in np.nonzero(b1[e] >= 0)[0]:
+                epd_tok[base + int(b1[e, s])] = int(sfd_tok[off[j] + s])
+        base += int((b1 >= 0).sum())
+    got = [epd_tok[r] for r in range(T * k)]
+    # stable sort by expert orders ties by flat index = token-ascending
+    assert got == tok[order].tolist()
+
+
+# ---------------------------------------------------------------- closed form, uniform routing
+@pytest.mark.parametrize("E,D,k", [(64, 4, 8), (64, 8, 8), (16, 4, 4), (64, 16, 6)])
+def test_replica_count_closed_form_uniform_subsets(E, D, k, golden_dir):
+    # uniformly random k-subsets: E[C_T] = D * (1 - C(E-G, k) / C(E, k))
+    T = 16384
+    G = E // D
+    rng = np.random.default_rng(4)
+    ids = np.argsort(rng.random((T, E)), axis=1)[:, :k].astype(np.int32)
+    w = np.full((T, k), 1.0 / k)
+    tr = occult_ref.moe_forward(np.zeros((T, 1)), ids, w, wl.contiguous_placement(E, D), D)
+    p_hit = 1 - math.comb(E - G, k) / math.comb(E, k)
+    mean = D * p_hit
+    sigma = math.sqrt(D * p_hit * (1 - p_hit))       # upper bound (negative correlation)
+    assert abs(tr.c_t - mean) < 4 * sigma / math.sqrt(T)
+    if (E, D, k) == (64, 4, 8):
+        # the paper measured 3.68 for trivial placement of OLMoE on 4 devices (Table 1);
+        # uniform routing predicts 3.659: same regime, within 1 %
+        rows = [l.split() for l in open(f"{golden_dir}/table1_replicas.txt") if l[0] != "#"]
+        measured = {r[0]: float(r[2]) for r in rows}["occult_trivial"]
+        assert abs(mean - measured) / measured < 0.01
+        assert abs(tr.c_t - measured) / measured < 0.02
+
+
+# ---------------------------------------------------------------- exactness (pruning off)
+@pytest.mark.parametrize("S", [0, 2])
+def test_deduplicated_layer_equals_textbook_layer(S):
+    shape = wl.LayerShape("t", T=96, d=32, f=48, E=12, S=S, k=3, D=3, dtype="f32", components=0)
+    wk = wl.make_workload(shape, seed=9)
+    ids, w = routing.route(wk.logits, shape.k, shape.D)
+    y_std = moe_std.moe_layer(wk.x, ids, w, wk.w_gate, wk.w_up, wk.w_down, shape.E, S)
+    y_loop = moe_std.moe_layer_loops(wk.x, ids, w, wk.w_gate, wk.w_up, wk.w_down, shape.E, S)
+    assert np.allclose(y_std, y_loop, rtol=1e-11, atol=1e-13)
+    for pos in (wl.contiguous_placement(12, 3), wl.random_placement(12, 3, seed=1),
+                np.arange(12, dtype=np.int32)):
+        D = 3
+        tr = occult_ref.moe_forward(wk.x, ids, w, pos, D, wk.w_gate, wk.w_up, wk.w_down, S)
+        assert np.allclose(tr.y, y_std, rtol=1e-10, atol=1e-12)    # placement never changes y
+    # standard dispatch = one device per expert: C_T = k exactly (Table 1, first column)
+    tr = occult_ref.moe_forward(wk.x, ids, w, np.arange(12, dtype=np.int32), 12,
+                                wk.w_gate, wk.w_up, wk.w_down, S)
+    assert tr.c_t == shape.k
+    assert np.allclose(tr.y, y_std, rtol=1e-10, atol=1e-12)
+
+
+def test_textbook_layer_one_token_one_expert_is_plain_swiglu():
+    rng = np.random.default_rng(0)
+    d, f = 8, 5
+    x = rng.standard_normal((1, d))
+    wg, wu, wd = rng.standard_normal((1, f, d)), rng.standard_normal((1, f, d)), \
+        rng.standard_normal((1, d, f))
+    y = moe_std.moe_layer(x, np.zeros((1, 1), np.int32), np.array([[0.25]]), wg, wu, wd, E=1)
+    g = wg[0] @ x[0]
+    want = 0.25 * (wd[0] @ (g / (1 + np.exp(-g)) * (wu[0] @ x[0])))
+    assert np.allclose(y[0], want, rtol=1e-13)
+    # silu closed-form values
+    assert moe_std.silu(np.array([0.0]))[0] == 0.0
+    assert np.isclose(moe_std.silu(np.array([1.0]))[0], 1 / (1 + math.exp(-1)))
+
+
+def test_bypass_path_is_bit_exact_against_direct_sum():
+    # expert e replaced by v -> c_e * v, integer hidden states, power-of-two gates:
+    # every partial sum is exact, so dispatch + merge + combine must give the direct sum bit for bit
+    E, D, k, T, d = 16, 4, 4, 211, 24
+    lg = wl.random_logits(T, E, seed=31)
+    pos = wl.random_placement(E, D, seed=3)
+    ids, _ = routing.route(lg, k, D, pos)
+    w = np.tile(np.array([0.5, 0.25, 0.125, 0.125]), (T, 1))
+    x = wl.integer_valued_rows(T, d, seed=1)
+    c = (np.arange(E) % 3 + 1).astype(np.float64)
+    tr = occult_ref.moe_forward(x, ids, w, pos, D, bypass_scale=c, acc=np.float32)
+    want = np.zeros((T, d), dtype=np.float64)
+    for t in range(T):
+        for s in range(k):
+            want[t] += w[t, s] * c[ids[t, s]] * x[t]
+    assert tr.y.dtype == np.float32
+    assert np.array_equal(tr.y.astype(np.float64), want)
+
+
+# ---------------------------------------------------------------- brute force on tiny inputs
+def test_brute_force_every_routing_of_tiny_layer():
+    E, D, k = 6, 3, 2
+    G = E // D
+    pos = np.array([4, 0, 3, 1, 5, 2], dtype=np.int32)
+    subsets = list(itertools.permutations(range(E), k))          # every ordered selection
+    ids = np.array(subsets, dtype=np.int32)
+    T = len(ids)
+    w = np.full((T, k), 0.5)
+    x = np.arange(T, dtype=np.float64)[:, None] + 1.0
+    tr = occult_ref.moe_forward(x, ids, w, pos, D, bypass_scale=np.ones(E))
+    dev_of = pos // G
+    row = 0
+    for j in range(D):
+        for t in range(T):
+            present = any(dev_of[e] == j for e in ids[t])
+            if present:
+                assert tr.brim_0[j, t] == row
+                assert tr.x_sfd[row, 0] == x[t, 0]
+                row += 1
+            else:
+                assert tr.brim_0[j, t] == -1
+    assert row == tr.n_sfd
+    assert np.array_equal(tr.y, x * 1.0)                           # gates sum to one, E_e = id
+    bytes_ = occult_ref.exchange_bytes(T, k, tr.n_sfd, row_bytes=8)
+    assert bytes_["bytes_std"] == 2 * T * k * 8 and bytes_["bytes_occ"] == 2 * tr.n_sfd * 8
+
+
+def test_config_workloads_replica_statistics():
+    # soft expectations on the synthetic prefill workload: skewed loads, C_T near the
+    # uniform-routing closed form (random router weights do not align with placement)
+    shape = wl.CONFIGS["prefill_bf16"]
+    wk = wl.make_workload(shape, with_experts=False)
+    ids, w = routing.route(wk.logits, shape.k, shape.D)
+    tr = occult_ref.moe_forward(np.zeros((shape.T, 1)), ids, w,
+                                wl.contiguous_placement(shape.E, shape.D), shape.D)
+    assert 5.2 < tr.c_t < 5.7
+    load = np.bincount(ids.reshape(-1), minlength=shape.E)
+    assert load.max() > 1.3 * load.mean() and load.min() < 0.7 * load.mean()
+    ids_p, w_p = routing.route(wk.logits, shape.k, shape.D, n_d=2, prune_mode=1)
+    tr_p = occult_ref.moe_forward(np.zeros((shape.T, 1)), ids_p, w_p,
+                                  wl.contiguous_placement(shape.E, shape.D), shape.D)
+    assert tr_p.c_t <= 2.0 and tr_p.c_t > 1.9
