@@ -1,0 +1,201 @@
+/*
+ * occult.h - C ABI of the MI355X (gfx950) library for the forward hot path of a
+ * collaboration-aware expert-parallel mixture-of-experts layer
+ * (Occult, arXiv 2505.13345).
+ *
+ * One GPU's share of the layer: the D devices of expert parallelism are simulated as
+ * groups of G = E / D experts on one GPU, the rows they would exchange are packed into
+ * per-device segments and counted, nothing crosses GPUs.
+ *
+ * Conventions for every call
+ *  - returns OCCULT_OK (0) or a negative OCCULT_E* code; never throws or aborts;
+ *    occult_last_error() gives a thread-local message for the last failure;
+ *  - "device ptr" = memory of the current HIP device, "host ptr" = ordinary host memory;
+ *  - data calls are asynchronous on the HIP stream passed as `stream` (a hipStream_t cast to
+ *    void*; NULL = the default stream), allocate nothing and never synchronise;
+ *    the caller owns every buffer and keeps it alive until the stream has passed the call;
+ *  - arguments are checked on the host before anything is launched (shape limits below);
+ *    NOT checked: router scores are finite, `ids` are in range and distinct per token,
+ *    `expert_pos` is a permutation of 0..E-1;
+ *  - rows of x / sfd / epd / y must start 16-byte aligned: (d * element size) % 16 == 0 and
+ *    (f * element size) % 16 == 0, base pointers 16-byte aligned.
+ *
+ * Notation (the paper's): T = tokens in ORI state, SFD = one replica of a token per distinct
+ * destination device (the all-to-all payload), EPD = one replica per (token, selected expert).
+ * N_sfd = number of SFD rows, N_epd = T * k.  Placement position P of an expert = device * G + slot.
+ */
+#ifndef OCCULT_H
+#define OCCULT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OCCULT_VERSION 100
+
+enum {
+  OCCULT_OK = 0,
+  OCCULT_EINVAL = -1,     /* an argument value is outside the documented range          */
+  OCCULT_ESHAPE = -2,     /* shapes are inconsistent (E % D, n_d * G < k, ...)           */
+  OCCULT_EALIGN = -3,     /* a row or pointer is not 16-byte aligned                     */
+  OCCULT_ENULLPTR = -4,   /* a required pointer is NULL                                  */
+  OCCULT_EWORKSPACE = -5, /* plan memory or workspace is smaller than occult_plan_sizes  */
+  OCCULT_EHIP = -6        /* a HIP runtime call or kernel launch reported an error       */
+};
+
+enum { OCCULT_F32 = 0, OCCULT_BF16 = 1 };
+
+/* Limits checked by every call. */
+#define OCCULT_MAX_E 256
+#define OCCULT_MAX_D 64
+#define OCCULT_MAX_K 32
+
+typedef void* occult_stream_t; /* a hipStream_t */
+
+/* Layer description.  Plain data; copied by value inside each call. */
+typedef struct occult_cfg {
+  int32_t T;          /* tokens (ORI rows), >= 0; T * k < 2^31                              */
+  int32_t d;          /* hidden size                                                        */
+  int32_t f;          /* expert intermediate size                                           */
+  int32_t E;          /* routed experts, 1..OCCULT_MAX_E, E % D == 0                        */
+  int32_t S;          /* shared experts applied to every token with weight 1 (0 = none)     */
+  int32_t k;          /* experts per token, 1..min(E, OCCULT_MAX_K)                          */
+  int32_t D;          /* simulated devices, 1..OCCULT_MAX_D                                  */
+  int32_t n_d;        /* collaboration pruning (paper Sec. 3.3): 0 = off, else each token may
+                         use at most n_d devices, 1..D, and n_d * (E/D) >= k                */
+  int32_t prune_mode; /* 1 = keep the n_d devices of highest summed gate score over the
+                         token's unpruned top-k; 2 = keep the first n_d distinct devices met
+                         walking the unpruned top-k in descending score (Sec. 3.3 wording)  */
+  int32_t renorm;     /* 1 = gates divided by their sum over the selected k                 */
+  int32_t dtype;      /* OCCULT_F32 or OCCULT_BF16: element type of x, weights, sfd, epd, y  */
+  int32_t reserved;
+  const int32_t* expert_pos; /* device ptr [E]: placement position of each expert
+                                (device = pos / G, slot = pos % G); NULL = contiguous, pos[e] = e */
+} occult_cfg_t;
+
+/* Dispatch plan: device tables, caller-allocated (one block of occult_plan_sizes() bytes carved
+ * by occult_plan_bind()).  Relation to the paper's re-index matrices (Sec. 3.1, App. A.2):
+ *   BRIM_0[j][t]            = tok_sfd_row[t * D + j]                  (global SFD row, -1 absent)
+ *   BRIM_1 of device j      : for SFD row r in [dev_offset[j], dev_offset[j+1]) and slot s,
+ *                             entry = (EPD row of (r, expert at P = j*G+s)) - exp_offset[j*G], or -1
+ *   brim_w                  = epd_gate[EPD row]
+ * Orders: SFD rows are device-major and token-ascending inside a device; EPD rows are
+ * position-major (device, slot) and SFD-row-ascending inside an expert.                     */
+typedef struct occult_plan {
+  uint64_t* tok_devmask;  /* [T]        bit j set = token has an expert on device j          */
+  int32_t*  dev_count;    /* [D]        SFD rows per device                                  */
+  int32_t*  dev_offset;   /* [D+1]      exclusive scan of dev_count; [D] = N_sfd             */
+  int32_t*  tok_sfd_row;  /* [T][D]     SFD row of token t on device j, -1 if absent         */
+  int32_t*  sfd_token;    /* [T*min(k,D)] token of each SFD row (first N_sfd entries valid)  */
+  int32_t*  exp_count;    /* [E]        EPD rows per placement position                      */
+  int32_t*  exp_offset;   /* [E+1]      exclusive scan of exp_count; [E] = T*k               */
+  int32_t*  pos_expert;   /* [E]        expert id sitting at each placement position         */
+  int32_t*  epd_sfd_row;  /* [T*k]      SFD row that feeds each EPD row (replication index)  */
+  float*    epd_gate;     /* [T*k]      routing weight of each EPD row                       */
+  int32_t*  sfd_epd_rows; /* [T*min(k,D)][min(k,G)] EPD rows of each SFD row, slot-ascending,
+                             -1 padded (the merge list of combine stage 1)                   */
+  uint64_t* counters;     /* [8]        0: N_sfd, 1: N_epd, 2: T*k (standard replica rows),
+                                        3: max dev_count, 4: max exp_count, 5..7: 0          */
+} occult_plan_t;
+
+/* Expert weights, device ptrs, element type cfg.dtype, K-contiguous ("out-major"):
+ *   w_gate [E+S][f][d], w_up [E+S][f][d], w_down [E+S][d][f]; experts E..E+S-1 are shared. */
+typedef struct occult_weights {
+  const void* w_gate;
+  const void* w_up;
+  const void* w_down;
+} occult_weights_t;
+
+/* Host-side statistics of one plan (paper Sec. 2.2: C_T = N_sfd / T, the mean replicas per
+ * token; byte counts are hidden rows over both trips: dispatch + return). */
+typedef struct occult_stats {
+  uint64_t n_sfd, n_epd, rows_std;
+  uint64_t max_dev_count, max_exp_count;
+  uint64_t bytes_occ;   /* 2 * N_sfd * d * element size                                    */
+  uint64_t bytes_std;   /* 2 * T * k * d * element size (k replicas per token)             */
+  uint64_t bytes_meta;  /* N_sfd * k * 8: ids and gates carried on the first trip          */
+  double   c_t;         /* N_sfd / T                                                        */
+} occult_stats_t;
+
+int occult_version(void);
+const char* occult_last_error(void);
+
+/* Sizes in bytes of the plan block and of the planner's scratch workspace for cfg. Host, pure. */
+int occult_plan_sizes(const occult_cfg_t* cfg, size_t* plan_bytes, size_t* workspace_bytes);
+
+/* Carve `plan_mem` (device ptr, 256-byte aligned, >= plan_bytes) into the tables of `out`
+ * (host struct).  Host, pure: touches no device memory. */
+int occult_plan_bind(const occult_cfg_t* cfg, void* plan_mem, size_t plan_bytes, occult_plan_t* out);
+
+/* Router (paper Eq. 1; Sec. 3.3 routing-score-based pruning).
+ * logits [T][E] f32 device ptr (router scores g(x)); outputs ids [T][k] i32 (slot 0 = highest
+ * score; equal scores -> lower expert index first) and w [T][k] f32 (softmax over all E experts
+ * at the selected ones, divided by their sum if cfg.renorm).  With cfg.n_d > 0 the selection is
+ * restricted to n_d devices as described at occult_cfg.  cfg.expert_pos is read when n_d > 0. */
+int occult_route(const occult_cfg_t* cfg, const float* logits, int32_t* ids, float* w,
+                 occult_stream_t stream);
+
+/* Planner (paper App. A.2 "Building BRIM_0" / "Building BRIM_1" for all D simulated devices at
+ * once; Sec. 2.2 replica count).  ids [T][k] i32, w [T][k] f32 device ptrs; fills every table of
+ * `plan`.  `ws` device ptr of >= workspace_bytes.  Bit-reproducible (no atomics). */
+int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
+                const occult_plan_t* plan, void* ws, size_t ws_bytes, occult_stream_t stream);
+
+/* Dispatch ORI -> SFD (paper App. A.2 "Dispatch"): sfd_x[tok_sfd_row[t][j]] = x[t] for every
+ * device j of token t.  x [T][d], sfd_x [>= N_sfd][d] (allocate T*min(k,D) rows), device ptrs. */
+int occult_dispatch(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* x, void* sfd_x,
+                    occult_stream_t stream);
+
+/* Expert computing (paper App. A.2 "SMM with Scattering" and the GEMM of "SMM with Merging"),
+ * SwiGLU experts: for EPD row r of the expert at position P with SFD source row s = epd_sfd_row[r]:
+ *   epd_h[r] = silu(W_gate sfd_x[s]) * (W_up sfd_x[s])      [N_epd][f]
+ *   epd_y[r] = W_down epd_h[r]                               [N_epd][d]
+ * (the SFD -> EPD replication happens in the first product's row gather; the reduction over
+ * a device's experts is occult_combine's first stage).  Shared experts, if S > 0:
+ *   h_shared[t] = concat_s silu(W_gate,s x[t]) * (W_up,s x[t])   [T][S*f]
+ *   y_shared[t] = sum_s W_down,s h_shared[t][s]                   [T][d]
+ * x, h_shared, y_shared may be NULL when S == 0.  bf16: MFMA with f32 accumulation, epd_h
+ * rounded to bf16; f32: plain f32 arithmetic.  All device ptrs. */
+int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                      const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
+                      void* h_shared, void* y_shared, occult_stream_t stream);
+
+/* Two-stage combine (paper Sec. 3.1 two-stage aggregation of Eq. 0; App. A.2 "Weight
+ * Modulation", the accumulation of "SMM with Merging", and "Combine").
+ * Stage 1 (on the device, before the return trip): sfd_y[r] = sum over the EPD rows q of SFD
+ *   row r, in slot order, of epd_gate[q] * epd_y[q] (f32 accumulation, stored in cfg.dtype:
+ *   this is the return payload).
+ * Stage 2 (after the return trip): y[t] = sum over devices j ascending of
+ *   sfd_y[tok_sfd_row[t][j]]  (+ y_shared[t] if not NULL), f32 accumulation.
+ * epd_y [N_epd][d], sfd_y [>= N_sfd][d], y [T][d]; device ptrs.  Order-fixed, no atomics. */
+int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_y,
+                   void* sfd_y, const void* y_shared, void* y, occult_stream_t stream);
+
+/* Co-activation counts (paper Preliminary, co-activation graph): C[i][j] = number of tokens
+ * whose selected experts include both i and j (diagonal = expert load).  ids [T][k], C [E][E]
+ * i32 device ptrs; accumulate = 0 overwrites C, 1 adds to it (profiling over batches). */
+int occult_coactivation(const occult_cfg_t* cfg, const int32_t* ids, int32_t* C, int accumulate,
+                        occult_stream_t stream);
+
+/* Greedy collaboration-aware placement (paper Sec. 3.2, Algorithm 1) on the host, in integer
+ * arithmetic.  C_host [E][E] i32 host ptr (diagonal ignored); needs E % D == 0 and E / D >= 2.
+ * Outputs, host ptrs: L_host [D][G] (experts of each device in slot order) and
+ * expert_pos_host [E].  Device 0 starts from the most co-activated pair (ties -> smallest (i, j));
+ * every later device starts from the unused expert with the smallest summed count to the placed
+ * experts; a device grows by the unused expert with the largest summed count to its own
+ * experts (ties -> lowest expert index). */
+int occult_placement_greedy(const int32_t* C_host, int32_t E, int32_t D, int32_t* L_host,
+                            int32_t* expert_pos_host);
+
+/* Copy the plan counters to the host and derive the statistics.  Synchronises `stream`
+ * (the only call that does). */
+int occult_plan_stats(const occult_cfg_t* cfg, const occult_plan_t* plan, occult_stats_t* out_host,
+                      occult_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OCCULT_H */

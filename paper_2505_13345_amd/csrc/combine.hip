@@ -1,0 +1,173 @@
+// occult_combine: the two-stage aggregation of Eq. 0 (paper Sec. 3.1; App. A.2 "Weight
+// Modulation", the accumulation of "SMM with Merging", and "Combine").
+//
+// Stage 1 is what each device does before the return trip: the outputs of a token's experts on
+// that device are weighted by their gates and summed (slot order, f32) into one SFD row, which
+// is stored in the layer's element type because it is the return payload.  Stage 2 is the
+// source rank after the return trip: a token's SFD rows are summed in ascending device order.
+//
+// The printed Combine re-reads the whole SFD tensor once per device.  Here one wavefront owns
+// one token and runs both stages back to back: the SFD row it has just rounded and stored is
+// added to the token's accumulator from registers, so sfd_y is written once and not read again.
+// Traffic per token: k EPD rows in, c_t SFD rows out, one ORI row out (+ one shared row in).
+// The arithmetic (orders, roundings) is that of the two separate stages; no atomics.
+#include "common.h"
+
+namespace occult {
+
+constexpr int kCombWaves = 4;
+
+template <bool BF16>
+struct Row;
+
+// bf16: a 16-byte vector = 8 elements
+template <>
+struct Row<true> {
+  static constexpr int kElems = 8;
+  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
+    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(base) + row * row_vecs + c);
+    out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x);
+    out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
+    out[4] = bf16_lo(v.z); out[5] = bf16_hi(v.z);
+    out[6] = bf16_lo(v.w); out[7] = bf16_hi(v.w);
+  }
+  // stores the rounded values and returns them in `vals`
+  __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
+    u32x4 v;
+    v.x = pack_bf16(vals[0], vals[1]);
+    v.y = pack_bf16(vals[2], vals[3]);
+    v.z = pack_bf16(vals[4], vals[5]);
+    v.w = pack_bf16(vals[6], vals[7]);
+    __builtin_nontemporal_store(v, static_cast<u32x4*>(base) + row * row_vecs + c);
+    vals[0] = bf16_lo(v.x); vals[1] = bf16_hi(v.x);
+    vals[2] = bf16_lo(v.y); vals[3] = bf16_hi(v.y);
+    vals[4] = bf16_lo(v.z); vals[5] = bf16_hi(v.z);
+    vals[6] = bf16_lo(v.w); vals[7] = bf16_hi(v.w);
+  }
+};
+
+// f32: a 16-byte vector = 4 elements
+template <>
+struct Row<false> {
+  static constexpr int kElems = 4;
+  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
+    const f32x4 v = __builtin_nontemporal_load(static_cast<const f32x4*>(base) + row * row_vecs + c);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  }
+  __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
+    f32x4 v;
+    v.x = vals[0]; v.y = vals[1]; v.z = vals[2]; v.w = vals[3];
+    __builtin_nontemporal_store(v, static_cast<f32x4*>(base) + row * row_vecs + c);
+  }
+};
+
+template <bool BF16, int VPL>
+__global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
+    const void* __restrict__ epd_y, void* __restrict__ sfd_y, const void* __restrict__ y_shared,
+    void* __restrict__ y, const int32_t* __restrict__ tok_sfd_row,
+    const int32_t* __restrict__ sfd_epd_rows, const float* __restrict__ epd_gate, int T, int D, int M1,
+    int row_vecs) {
+  using R = Row<BF16>;
+  constexpr int NE = R::kElems;
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kCombWaves + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * kCombWaves;
+  for (int t = wave; t < T; t += nwaves) {
+    float acc[VPL][NE];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+#pragma unroll
+      for (int e = 0; e < NE; ++e) acc[i][e] = 0.0f;
+
+    for (int j = 0; j < D; ++j) {
+      const int r = tok_sfd_row[(size_t)t * D + j];   // wave-uniform
+      if (r < 0) continue;
+      float part[VPL][NE];
+#pragma unroll
+      for (int i = 0; i < VPL; ++i)
+#pragma unroll
+        for (int e = 0; e < NE; ++e) part[i][e] = 0.0f;
+      // stage 1: gate-weighted sum of this device's expert outputs, slot order
+      for (int m = 0; m < M1; ++m) {
+        const int q = sfd_epd_rows[(size_t)r * M1 + m];
+        if (q < 0) break;
+        const float g = epd_gate[q];
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+          const int c = lane + 64 * i;
+          if (c < row_vecs) {
+            float v[NE];
+            R::load(epd_y, (size_t)q, row_vecs, c, v);
+#pragma unroll
+            for (int e = 0; e < NE; ++e) part[i][e] = fmaf(g, v[e], part[i][e]);
+          }
+        }
+      }
+      // the return payload, then stage 2 on the rounded values
+#pragma unroll
+      for (int i = 0; i < VPL; ++i) {
+        const int c = lane + 64 * i;
+        if (c < row_vecs) {
+          R::store_round(sfd_y, (size_t)r, row_vecs, c, part[i]);
+#pragma unroll
+          for (int e = 0; e < NE; ++e) acc[i][e] += part[i][e];
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < row_vecs) {
+        if (y_shared) {
+          float v[NE];
+          R::load(y_shared, (size_t)t, row_vecs, c, v);
+#pragma unroll
+          for (int e = 0; e < NE; ++e) acc[i][e] += v[e];
+        }
+        R::store_round(y, (size_t)t, row_vecs, c, acc[i]);
+      }
+    }
+  }
+}
+
+}  // namespace occult
+
+using namespace occult;
+
+extern "C" int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_y,
+                              void* sfd_y, const void* y_shared, void* y, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  if (c.T == 0) return OCCULT_OK;
+  OCC_REQUIRE(plan && plan->tok_sfd_row && plan->sfd_epd_rows && plan->epd_gate, OCCULT_ENULLPTR,
+              "plan or one of its tables is NULL");
+  OCC_REQUIRE(epd_y && sfd_y && y, OCCULT_ENULLPTR, "epd_y, sfd_y or y is NULL");
+  const size_t row_bytes = (size_t)c.d * elem_size(c);
+  OCC_REQUIRE(row_bytes % 16 == 0, OCCULT_EALIGN, "row of %zu bytes is not a multiple of 16", row_bytes);
+  OCC_REQUIRE(aligned16(epd_y) && aligned16(sfd_y) && aligned16(y) && aligned16(y_shared), OCCULT_EALIGN,
+              "a buffer is not 16-byte aligned");
+  const int row_vecs = (int)(row_bytes / 16);
+  const int vpl = (row_vecs + 63) / 64;
+  OCC_REQUIRE(vpl <= 8, OCCULT_EINVAL, "rows longer than 8 KiB are not supported by combine (d=%d)", c.d);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const dim3 grid((c.T + kCombWaves - 1) / kCombWaves), block(kCombWaves * 64);
+  const int M1 = merge_width(c);
+#define OCC_COMB(B, N)                                                                             \
+  hipLaunchKernelGGL((combine_kernel<B, N>), grid, block, 0, s, epd_y, sfd_y, y_shared, y,         \
+                     plan->tok_sfd_row, plan->sfd_epd_rows, plan->epd_gate, c.T, c.D, M1, row_vecs)
+  if (c.dtype == OCCULT_BF16) {
+    if (vpl <= 1) OCC_COMB(true, 1);
+    else if (vpl <= 2) OCC_COMB(true, 2);
+    else if (vpl <= 4) OCC_COMB(true, 4);
+    else OCC_COMB(true, 8);
+  } else {
+    if (vpl <= 1) OCC_COMB(false, 1);
+    else if (vpl <= 2) OCC_COMB(false, 2);
+    else if (vpl <= 4) OCC_COMB(false, 4);
+    else OCC_COMB(false, 8);
+  }
+#undef OCC_COMB
+  OCC_LAUNCH_CHECK("combine_kernel");
+  return OCCULT_OK;
+}

@@ -1,0 +1,94 @@
+// occult_dispatch: ORI -> SFD pack (paper App. A.2 "Dispatch"; Sec. 3.1: one replica of a token
+// per distinct destination device).
+//
+// The printed kernel walks (device, token-tile) pairs and so reads every token row once per
+// device.  Here the loop is token-major: a wavefront reads row t once with 16-byte lane loads,
+// keeps it in registers, and stores it to each of the token's <= min(k, D) SFD rows, so the
+// HBM traffic is (1 + c_t) rows per token.  Pure copy: bandwidth bound.
+#include "common.h"
+
+namespace occult {
+
+constexpr int kDispWaves = 4;   // waves (tokens in flight) per block
+
+// VPL = 16-byte vectors per lane; row_vecs = d * es / 16 <= 64 * VPL
+template <int VPL>
+__global__ __launch_bounds__(kDispWaves * 64) void dispatch_kernel(
+    const u32x4* __restrict__ x, u32x4* __restrict__ sfd_x, const int32_t* __restrict__ tok_sfd_row,
+    int T, int D, int row_vecs) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kDispWaves + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * kDispWaves;
+  for (int t = wave; t < T; t += nwaves) {
+    u32x4 v[VPL];
+    const u32x4* src = x + (size_t)t * row_vecs;
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+      const int c = lane + 64 * i;
+      if (c < row_vecs) v[i] = __builtin_nontemporal_load(src + c);
+    }
+    for (int j = 0; j < D; ++j) {
+      const int r = tok_sfd_row[(size_t)t * D + j];   // wave-uniform
+      if (r < 0) continue;
+      u32x4* dst = sfd_x + (size_t)r * row_vecs;
+#pragma unroll
+      for (int i = 0; i < VPL; ++i) {
+        const int c = lane + 64 * i;
+        if (c < row_vecs) __builtin_nontemporal_store(v[i], dst + c);
+      }
+    }
+  }
+}
+
+// rows longer than 64 * 8 vectors (8 KiB): plain strided loop, row re-read per destination
+__global__ __launch_bounds__(kDispWaves * 64) void dispatch_kernel_long(
+    const u32x4* __restrict__ x, u32x4* __restrict__ sfd_x, const int32_t* __restrict__ tok_sfd_row,
+    int T, int D, int row_vecs) {
+  const int lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kDispWaves + (threadIdx.x >> 6);
+  const int nwaves = gridDim.x * kDispWaves;
+  for (int t = wave; t < T; t += nwaves) {
+    const u32x4* src = x + (size_t)t * row_vecs;
+    for (int j = 0; j < D; ++j) {
+      const int r = tok_sfd_row[(size_t)t * D + j];
+      if (r < 0) continue;
+      u32x4* dst = sfd_x + (size_t)r * row_vecs;
+      for (int c = lane; c < row_vecs; c += 64) dst[c] = src[c];
+    }
+  }
+}
+
+}  // namespace occult
+
+using namespace occult;
+
+extern "C" int occult_dispatch(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* x,
+                               void* sfd_x, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  if (c.T == 0) return OCCULT_OK;
+  OCC_REQUIRE(plan && plan->tok_sfd_row, OCCULT_ENULLPTR, "plan or plan->tok_sfd_row is NULL");
+  OCC_REQUIRE(x && sfd_x, OCCULT_ENULLPTR, "x or sfd_x is NULL");
+  const size_t row_bytes = (size_t)c.d * elem_size(c);
+  OCC_REQUIRE(row_bytes % 16 == 0, OCCULT_EALIGN, "row of %zu bytes is not a multiple of 16", row_bytes);
+  OCC_REQUIRE(aligned16(x) && aligned16(sfd_x), OCCULT_EALIGN, "x or sfd_x is not 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int row_vecs = (int)(row_bytes / 16);
+  const int vpl = (row_vecs + 63) / 64;
+  const int blocks = (c.T + kDispWaves - 1) / kDispWaves;
+  const dim3 grid(blocks), block(kDispWaves * 64);
+  const u32x4* xs = static_cast<const u32x4*>(x);
+  u32x4* ds = static_cast<u32x4*>(sfd_x);
+#define OCC_DISP(N) \
+  hipLaunchKernelGGL(dispatch_kernel<N>, grid, block, 0, s, xs, ds, plan->tok_sfd_row, c.T, c.D, row_vecs)
+  if (vpl <= 1) OCC_DISP(1);
+  else if (vpl <= 2) OCC_DISP(2);
+  else if (vpl <= 4) OCC_DISP(4);
+  else if (vpl <= 8) OCC_DISP(8);
+  else
+    hipLaunchKernelGGL(dispatch_kernel_long, grid, block, 0, s, xs, ds, plan->tok_sfd_row, c.T, c.D, row_vecs);
+#undef OCC_DISP
+  OCC_LAUNCH_CHECK("dispatch_kernel");
+  return OCCULT_OK;
+}

@@ -1,0 +1,263 @@
+// occult_plan: the dispatch plan for all D simulated devices at once
+// (paper App. A.2 "Building BRIM_0" and "Building BRIM_1"; Sec. 2.2 replica count).
+//
+// The printed builders are sequential counters: BRIM_0 numbers (device, token) pairs
+// device-major / token-ascending, BRIM_1 numbers (local expert, SFD row) pairs expert-major /
+// row-ascending.  Both are stable ranks, so they are computed here without atomics:
+//   pass 1  plan_count : one token per thread; per block, how many of its 256 tokens touch each
+//                        device and each placement position (wave ballots + popcounts, LDS);
+//   pass 2  plan_scan  : one block turns the [blocks][D+E] counts into exclusive bases
+//                        (column scan over blocks, then a scan over devices / positions);
+//   pass 3  plan_fill  : every block repeats its ballots and writes the rank-addressed tables.
+// Inside a block the order is wave-major then lane = token-ascending, which is the order the
+// sequential counters would visit.  Every table is therefore bit-reproducible.
+#include "common.h"
+
+namespace occult {
+
+constexpr int kTPB = kPlanTokensPerBlock;   // 256 threads = 4 waves, one token per thread
+constexpr int kWavesPerBlock = kTPB / 64;
+constexpr int kMaxCols = OCCULT_MAX_D + OCCULT_MAX_E;
+
+struct TokenBits {
+  unsigned long long dev;      // bit j: token has an expert on device j
+  unsigned long long pos[4];   // bit P: token has the expert at placement position P
+};
+
+__device__ __forceinline__ TokenBits token_bits(const int32_t* __restrict__ ids, int t, int T, int k,
+                                                int G, const int* s_pos) {
+  TokenBits b;
+  b.dev = 0;
+  b.pos[0] = b.pos[1] = b.pos[2] = b.pos[3] = 0;
+  if (t < T) {
+    for (int s = 0; s < k; ++s) {
+      const int P = s_pos[ids[(size_t)t * k + s]];
+      b.dev |= 1ull << (P / G);
+      const unsigned long long bit = 1ull << (P & 63);
+      const int word = P >> 6;
+      b.pos[0] |= (word == 0) ? bit : 0ull;
+      b.pos[1] |= (word == 1) ? bit : 0ull;
+      b.pos[2] |= (word == 2) ? bit : 0ull;
+      b.pos[3] |= (word == 3) ? bit : 0ull;
+    }
+  }
+  return b;
+}
+
+__device__ __forceinline__ bool has_pos(const TokenBits& b, int P) {
+  const int word = P >> 6;
+  const unsigned long long m =
+      word == 0 ? b.pos[0] : (word == 1 ? b.pos[1] : (word == 2 ? b.pos[2] : b.pos[3]));
+  return (m >> (P & 63)) & 1ull;
+}
+
+// per-wave counts of the block's tokens per device and per position -> s_cnt[wave][col]
+__device__ __forceinline__ void wave_counts(const TokenBits& b, int D, int E, int wave, int lane,
+                                            int (*s_cnt)[kMaxCols]) {
+  for (int j = 0; j < D; ++j) {
+    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
+    if (lane == 0) s_cnt[wave][j] = __popcll(m);
+  }
+  for (int P = 0; P < E; ++P) {
+    const unsigned long long m = __ballot(has_pos(b, P));
+    if (lane == 0) s_cnt[wave][D + P] = __popcll(m);
+  }
+}
+
+__global__ __launch_bounds__(kTPB) void plan_count(const int32_t* __restrict__ ids, int T, int k, int E,
+                                                   int D, int G, const int32_t* __restrict__ expert_pos,
+                                                   uint64_t* __restrict__ tok_devmask,
+                                                   int32_t* __restrict__ blk_cnt) {
+  __shared__ int s_pos[OCCULT_MAX_E];
+  __shared__ int s_cnt[kWavesPerBlock][kMaxCols];
+  for (int e = threadIdx.x; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
+  __syncthreads();
+  const int t = blockIdx.x * kTPB + threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
+  if (t < T) tok_devmask[t] = b.dev;
+  wave_counts(b, D, E, wave, lane, s_cnt);
+  __syncthreads();
+  const int C = D + E;
+  for (int c = threadIdx.x; c < C; c += kTPB) {
+    int sum = 0;
+#pragma unroll
+    for (int wv = 0; wv < kWavesPerBlock; ++wv) sum += s_cnt[wv][c];
+    blk_cnt[(size_t)blockIdx.x * C + c] = sum;
+  }
+}
+
+// One block of 1024 threads.  Thread (part, c) owns rows [part*rpp, (part+1)*rpp) of column c.
+constexpr int kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void plan_scan(
+    int32_t* __restrict__ blk_cnt, int nblk, int T, int k, int E, int D, int G,
+    const int32_t* __restrict__ expert_pos, int32_t* __restrict__ dev_count,
+    int32_t* __restrict__ dev_offset, int32_t* __restrict__ exp_count, int32_t* __restrict__ exp_offset,
+    int32_t* __restrict__ pos_expert, uint64_t* __restrict__ counters) {
+  __shared__ int s_part[kScanThreads];       // [parts][C] partial column sums
+  __shared__ int s_total[kMaxCols];          // column totals
+  __shared__ int s_start[kMaxCols + 2];      // exclusive scans: devices, then positions
+  const int C = D + E;
+  const int parts = kScanThreads / C;        // >= 3 since C <= 320
+  const int rpp = (nblk + parts - 1) / parts;
+  const int part = threadIdx.x / C, c = threadIdx.x % C;
+  const bool active = part < parts;
+  const int r0 = part * rpp, r1 = min(nblk, r0 + rpp);
+
+  int sum = 0;
+  if (active)
+    for (int r = r0; r < r1; ++r) sum += blk_cnt[(size_t)r * C + c];
+  if (active) s_part[part * C + c] = sum;
+  __syncthreads();
+
+  int base = 0;   // sum of this column over the parts before mine
+  if (active)
+    for (int p = 0; p < part; ++p) base += s_part[p * C + c];
+  if (threadIdx.x < C) {
+    int tot = 0;
+    for (int p = 0; p < parts; ++p) tot += s_part[p * C + threadIdx.x];
+    s_total[threadIdx.x] = tot;
+  }
+  __syncthreads();
+
+  // exclusive scans over devices and over positions (<= 64 + 256 entries): one thread each
+  if (threadIdx.x == 0) {
+    int run = 0, mx = 0;
+    for (int j = 0; j < D; ++j) {
+      s_start[j] = run;
+      dev_count[j] = s_total[j];
+      dev_offset[j] = run;
+      mx = max(mx, s_total[j]);
+      run += s_total[j];
+    }
+    dev_offset[D] = run;
+    counters[0] = (uint64_t)run;
+    counters[3] = (uint64_t)mx;
+  } else if (threadIdx.x == 64) {
+    int run = 0, mx = 0;
+    for (int P = 0; P < E; ++P) {
+      s_start[D + P] = run;
+      exp_count[P] = s_total[D + P];
+      exp_offset[P] = run;
+      mx = max(mx, s_total[D + P]);
+      run += s_total[D + P];
+    }
+    exp_offset[E] = run;
+    counters[1] = (uint64_t)run;
+    counters[2] = (uint64_t)T * (uint64_t)k;
+    counters[4] = (uint64_t)mx;
+    counters[5] = counters[6] = counters[7] = 0;
+  } else if (threadIdx.x >= 128 && threadIdx.x < 128 + E) {
+    const int e = threadIdx.x - 128;
+    pos_expert[expert_pos ? expert_pos[e] : e] = e;
+  }
+  // E can exceed the 896 threads after 128 only if E > 896: not possible (E <= 256)
+  __syncthreads();
+
+  if (active) {
+    int run = s_start[c] + base;
+    for (int r = r0; r < r1; ++r) {
+      const int v = blk_cnt[(size_t)r * C + c];
+      blk_cnt[(size_t)r * C + c] = run;   // count -> first rank of this block in this column
+      run += v;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kTPB) void plan_fill(
+    const int32_t* __restrict__ ids, const float* __restrict__ w, int T, int k, int E, int D, int G,
+    int M1, const int32_t* __restrict__ expert_pos, const int32_t* __restrict__ blk_base,
+    int32_t* __restrict__ tok_sfd_row, int32_t* __restrict__ sfd_token,
+    int32_t* __restrict__ epd_sfd_row, float* __restrict__ epd_gate,
+    int32_t* __restrict__ sfd_epd_rows) {
+  __shared__ int s_pos[OCCULT_MAX_E];
+  __shared__ int s_cnt[kWavesPerBlock][kMaxCols];
+  for (int e = threadIdx.x; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
+  __syncthreads();
+  const int t = blockIdx.x * kTPB + threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
+  wave_counts(b, D, E, wave, lane, s_cnt);
+  __syncthreads();
+
+  const int C = D + E;
+  const int32_t* base = blk_base + (size_t)blockIdx.x * C;
+  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+
+  for (int j = 0; j < D; ++j) {
+    const bool on = (b.dev >> j) & 1ull;
+    const unsigned long long m = __ballot(on);
+    int before = 0;
+    for (int wv = 0; wv < wave; ++wv) before += s_cnt[wv][j];
+    const int r = on ? base[j] + before + __popcll(m & lt) : -1;
+    if (t < T) tok_sfd_row[(size_t)t * D + j] = r;
+    if (on) sfd_token[r] = t;
+
+    int filled = 0;   // merge-list entries of SFD row r written so far
+    for (int sl = 0; sl < G; ++sl) {
+      const int P = j * G + sl;
+      const bool hit = has_pos(b, P);
+      const unsigned long long me = __ballot(hit);
+      if (me == 0ull) continue;   // wave-uniform
+      int pbefore = 0;
+      for (int wv = 0; wv < wave; ++wv) pbefore += s_cnt[wv][D + P];
+      if (hit) {
+        const int q = base[D + P] + pbefore + __popcll(me & lt);
+        float gate = 0.0f;
+        for (int s = 0; s < k; ++s)
+          if (s_pos[ids[(size_t)t * k + s]] == P) gate = w[(size_t)t * k + s];
+        epd_sfd_row[q] = r;
+        epd_gate[q] = gate;
+        sfd_epd_rows[(size_t)r * M1 + filled] = q;
+        ++filled;
+      }
+    }
+    if (on)
+      for (int i = filled; i < M1; ++i) sfd_epd_rows[(size_t)r * M1 + i] = -1;
+  }
+}
+
+size_t plan_workspace_bytes(const occult_cfg_t& c);
+
+}  // namespace occult
+
+using namespace occult;
+
+extern "C" int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
+                           const occult_plan_t* plan, void* ws, size_t ws_bytes, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  OCC_REQUIRE(plan, OCCULT_ENULLPTR, "plan is NULL");
+  const occult_plan_t p = *plan;
+  OCC_REQUIRE(p.tok_devmask && p.dev_count && p.dev_offset && p.tok_sfd_row && p.sfd_token &&
+                  p.exp_count && p.exp_offset && p.pos_expert && p.epd_sfd_row && p.epd_gate &&
+                  p.sfd_epd_rows && p.counters,
+              OCCULT_ENULLPTR, "a plan table is NULL (use occult_plan_bind)");
+  OCC_REQUIRE(ws, OCCULT_ENULLPTR, "workspace is NULL");
+  OCC_REQUIRE(ws_bytes >= plan_workspace_bytes(c), OCCULT_EWORKSPACE, "workspace of %zu bytes < required %zu",
+              ws_bytes, plan_workspace_bytes(c));
+  OCC_REQUIRE(c.T == 0 || (ids && w), OCCULT_ENULLPTR, "ids or w is NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int G = c.E / c.D;
+  const int nblk = (c.T + kTPB - 1) / kTPB;
+  int32_t* blk = static_cast<int32_t*>(ws);
+  if (nblk > 0) {
+    hipLaunchKernelGGL(plan_count, dim3(nblk), dim3(kTPB), 0, s, ids, c.T, c.k, c.E, c.D, G, c.expert_pos,
+                       p.tok_devmask, blk);
+    OCC_LAUNCH_CHECK("plan_count");
+  }
+  // with T == 0 the scan still writes zero counts and offsets
+  hipLaunchKernelGGL(plan_scan, dim3(1), dim3(kScanThreads), 0, s, blk, nblk, c.T, c.k, c.E, c.D, G,
+                     c.expert_pos, p.dev_count, p.dev_offset, p.exp_count, p.exp_offset, p.pos_expert,
+                     p.counters);
+  OCC_LAUNCH_CHECK("plan_scan");
+  if (nblk > 0) {
+    hipLaunchKernelGGL(plan_fill, dim3(nblk), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G,
+                       merge_width(c), c.expert_pos, blk, p.tok_sfd_row, p.sfd_token, p.epd_sfd_row,
+                       p.epd_gate, p.sfd_epd_rows);
+    OCC_LAUNCH_CHECK("plan_fill");
+  }
+  return OCCULT_OK;
+}

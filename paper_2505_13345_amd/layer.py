@@ -1,0 +1,101 @@
+"""Device buffers for one layer and the call sequence of its forward hot path.
+
+Memory plumbing only: torch allocates the worst-case-sized buffers once (N_sfd <= T*min(k, D),
+N_epd = T*k), every step is one call into the C library on the current stream, and nothing here
+synchronises or computes.  Table views onto the plan block are for tests and reports.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class OccultLayer:
+    def __init__(self, T, d, f, E, S, k, D, dtype="bf16", n_d=0, prune_mode=1, renorm=1,
+                 expert_pos=None, device="cuda:0", with_ffn=True):
+        B.load_library()          # fail early and loudly if the HIP library is missing
+        self.device = torch.device(device)
+        self.shape = dict(T=T, d=d, f=f, E=E, S=S, k=k, D=D)
+        self.dtype_name = dtype
+        self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        dev = self.device
+        self.expert_pos = None
+        if expert_pos is not None:
+            self.expert_pos = torch.as_tensor(expert_pos, dtype=torch.int32).to(dev).contiguous()
+        self.cfg = B.make_cfg(T, d, f, E, S, k, D, dtype, n_d, prune_mode, renorm, self.expert_pos)
+        plan_bytes, ws_bytes = B.occult_plan_sizes(self.cfg)
+        self.plan_mem = torch.zeros(plan_bytes, dtype=torch.uint8, device=dev)
+        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+        self.plan = B.occult_plan_bind(self.cfg, self.plan_mem)
+        n_sfd_max = T * min(k, D)
+        self.n_sfd_max = n_sfd_max
+        self.ids = torch.zeros((T, k), dtype=torch.int32, device=dev)
+        self.w = torch.zeros((T, k), dtype=torch.float32, device=dev)
+        self.sfd_x = torch.zeros((n_sfd_max, d), dtype=self.tdtype, device=dev)
+        self.sfd_y = torch.zeros((n_sfd_max, d), dtype=self.tdtype, device=dev)
+        self.y = torch.zeros((T, d), dtype=self.tdtype, device=dev)
+        self.epd_h = self.epd_y = self.h_shared = self.y_shared = None
+        if with_ffn:
+            self.epd_h = torch.zeros((T * k, f), dtype=self.tdtype, device=dev)
+            self.epd_y = torch.zeros((T * k, d), dtype=self.tdtype, device=dev)
+            if S > 0:
+                self.h_shared = torch.zeros((T, S * f), dtype=self.tdtype, device=dev)
+                self.y_shared = torch.zeros((T, d), dtype=self.tdtype, device=dev)
+
+    # ---- steps (each = one library call on the current stream) -------------------------------
+    def route(self, logits):
+        B.occult_route(self.cfg, logits, self.ids, self.w)
+
+    def make_plan(self, ids=None, w=None):
+        B.occult_plan(self.cfg, self.ids if ids is None else ids, self.w if w is None else w,
+                      self.plan, self.ws)
+
+    def dispatch(self, x):
+        B.occult_dispatch(self.cfg, self.plan, x, self.sfd_x)
+
+    def expert_ffn(self, x, w_gate, w_up, w_down):
+        B.occult_expert_ffn(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h,
+                            self.epd_y, self.h_shared, self.y_shared)
+
+    def combine(self, epd_y=None):
+        B.occult_combine(self.cfg, self.plan, self.epd_y if epd_y is None else epd_y, self.sfd_y,
+                         self.y_shared, self.y)
+
+    def forward(self, logits, x, w_gate, w_up, w_down):
+        self.route(logits)
+        self.make_plan()
+        self.dispatch(x)
+        self.expert_ffn(x, w_gate, w_up, w_down)
+        self.combine()
+        return self.y
+
+    def stats(self):
+        return B.occult_plan_stats(self.cfg, self.plan)
+
+    # ---- views onto the plan block ------------------------------------------------------------
+    def _view(self, field, count, dtype):
+        base = self.plan_mem.data_ptr()
+        off = getattr(self.plan, field) - base
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        return self.plan_mem[off:off + nbytes].view(dtype)
+
+    def tables(self):
+        s = self.shape
+        T, E, D, k = s["T"], s["E"], s["D"], s["k"]
+        m1 = min(k, E // D)
+        i32 = torch.int32
+        return {
+            "tok_devmask": self._view("tok_devmask", T, torch.int64),
+            "dev_count": self._view("dev_count", D, i32),
+            "dev_offset": self._view("dev_offset", D + 1, i32),
+            "tok_sfd_row": self._view("tok_sfd_row", T * D, i32).view(T, D),
+            "sfd_token": self._view("sfd_token", self.n_sfd_max, i32),
+            "exp_count": self._view("exp_count", E, i32),
+            "exp_offset": self._view("exp_offset", E + 1, i32),
+            "pos_expert": self._view("pos_expert", E, i32),
+            "epd_sfd_row": self._view("epd_sfd_row", T * k, i32),
+            "epd_gate": self._view("epd_gate", T * k, torch.float32),
+            "sfd_epd_rows": self._view("sfd_epd_rows", self.n_sfd_max * m1, i32).view(self.n_sfd_max, m1),
+            "counters": self._view("counters", 8, torch.int64),
+        }

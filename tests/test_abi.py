@@ -1,0 +1,104 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, validates
+arguments before touching a GPU, lays the plan block out as documented, and its host-side
+placement equals the oracle's Algorithm 1.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from inputs import workloads as wl
+from oracle import collaboration, routing
+from paper_2505_13345_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "occult.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(occult_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert lib.occult_version() == 100
+
+
+def test_cfg_validation_reports_errors_without_a_gpu(lib):
+    good = dict(T=64, d=128, f=256, E=16, S=0, k=4, D=4, dtype="f32")
+    pb, wb = B.occult_plan_sizes(B.make_cfg(**good))
+    assert pb > 0 and wb > 0 and pb % 256 == 0
+    cases = [
+        (dict(good, D=5), -2),            # E % D
+        (dict(good, k=17), -1),           # k > E
+        (dict(good, E=512, D=4), -1),     # E above the limit
+        (dict(good, n_d=1, k=8), -2),     # pruned range cannot hold k
+        (dict(good, n_d=2, prune_mode=3), -1),
+        (dict(good, T=-1), -1),
+        (dict(good, renorm=2), -1),
+    ]
+    for kw, code in cases:
+        with pytest.raises(B.OccultError) as ei:
+            B.occult_plan_sizes(B.make_cfg(**kw))
+        assert ei.value.code == code
+        assert len(B.occult_last_error()) > 0
+    # NULL pointers are refused before any launch
+    cfg = B.make_cfg(**good)
+    rc = lib.occult_route(ctypes.byref(cfg), None, None, None, None)
+    assert rc == -4
+    rc = lib.occult_dispatch(ctypes.byref(cfg), None, None, None, None)
+    assert rc == -4
+
+
+def test_plan_bind_layout_is_aligned_and_disjoint(lib):
+    cfg = B.make_cfg(T=1000, d=64, f=64, E=60, S=0, k=4, D=4, dtype="bf16")
+    pb, _ = B.occult_plan_sizes(cfg)
+    base = 0x10000000
+    plan = B.occult_plan_t()
+    rc = lib.occult_plan_bind(ctypes.byref(cfg), base, pb, ctypes.byref(plan))
+    assert rc == 0
+    T, D, E, k = 1000, 4, 60, 4
+    sizes = dict(tok_devmask=T * 8, dev_count=D * 4, dev_offset=(D + 1) * 4, tok_sfd_row=T * D * 4,
+                 sfd_token=T * 4 * 4, exp_count=E * 4, exp_offset=(E + 1) * 4, pos_expert=E * 4,
+                 epd_sfd_row=T * k * 4, epd_gate=T * k * 4, sfd_epd_rows=T * 4 * 4 * 4, counters=64)
+    spans = []
+    for name, sz in sizes.items():
+        p = getattr(plan, name)
+        assert p % 256 == 0 and base <= p and p + sz <= base + pb
+        spans.append((p, p + sz))
+    spans.sort()
+    for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+        assert a1 <= b0
+    assert lib.occult_plan_bind(ctypes.byref(cfg), base + 8, pb, ctypes.byref(plan)) == -3
+    assert lib.occult_plan_bind(ctypes.byref(cfg), base, pb - 1, ctypes.byref(plan)) == -5
+
+
+@pytest.mark.parametrize("E,D,k,seed", [(16, 4, 4, 0), (64, 16, 6, 1), (60, 4, 4, 2), (12, 6, 2, 3)])
+def test_host_placement_equals_oracle_algorithm(E, D, k, seed):
+    ids, _ = routing.route(wl.random_logits(3000, E, seed=seed, scale=2.0), k, D)
+    C = collaboration.coactivation(ids, E)
+    L_ref, pos_ref = collaboration.greedy_placement(C, D)
+    L, pos = B.occult_placement_greedy(C.astype(np.int32), D)
+    assert L.tolist() == L_ref
+    assert pos.tolist() == pos_ref.tolist()
+    # ties everywhere: constant matrix
+    L, pos = B.occult_placement_greedy(np.ones((E, E), dtype=np.int32), D)
+    L_ref, pos_ref = collaboration.greedy_placement(np.ones((E, E), dtype=np.int64), D)
+    assert L.tolist() == L_ref and pos.tolist() == pos_ref.tolist()
+
+
+def test_host_placement_rejects_bad_shapes():
+    with pytest.raises(B.OccultError):
+        B.occult_placement_greedy(np.zeros((8, 8), dtype=np.int32), 8)     # one expert per device
+    with pytest.raises(B.OccultError):
+        B.occult_placement_greedy(np.zeros((8, 8), dtype=np.int32), 3)

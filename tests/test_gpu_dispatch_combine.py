@@ -1,0 +1,123 @@
+"""GPU parity for occult_dispatch and occult_combine.  Dispatch is a copy: bit-exact.  Combine is
+checked bit-exactly with inputs whose every partial sum is exactly representable (small-integer
+rows, power-of-two gates, the expert replaced by a per-expert integer scale), and within the
+floating-point bars on random data against the oracle's two-stage sums."""
+import numpy as np
+import pytest
+import torch
+
+from inputs import workloads as wl
+from oracle import occult_ref, routing
+from paper_2505_13345_amd.layer import OccultLayer
+from tests.helpers import bf16_errors, f32_rel_error, require_gpu, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # E, D, k, T, d, dtype, placement
+    (16, 4, 4, 211, 128, "f32", "random"),
+    (16, 4, 4, 256, 128, "bf16", "contig"),
+    (60, 4, 4, 128, 2048, "bf16", "contig"),
+    (64, 8, 8, 1500, 2048, "bf16", "random"),
+    (64, 16, 6, 1027, 2048, "bf16", "random"),
+    (64, 64, 8, 300, 512, "bf16", "contig"),
+    (8, 2, 2, 77, 8, "bf16", "contig"),          # 16-byte rows
+    (8, 2, 2, 77, 4096, "bf16", "contig"),       # 8 KiB rows
+    (8, 2, 2, 33, 1032, "f32", "random"),        # ragged vector count per lane
+]
+
+
+@pytest.mark.parametrize("E,D,k,T,d,dtype,placement", CASES)
+def test_dispatch_and_combine_bit_exact_on_exact_inputs(E, D, k, T, d, dtype, placement):
+    say(f"dispatch/combine exact case E={E} D={D} k={k} T={T} d={d} {dtype} {placement}")
+    dev = require_gpu()
+    lg = wl.random_logits(T, E, seed=T + d)
+    pos = None if placement == "contig" else wl.random_placement(E, D, seed=E)
+    pos_arr = wl.contiguous_placement(E, D) if pos is None else pos
+    ids, _ = routing.route(lg, k, D, pos)
+    # gates with quantum 1/8 that sum to one: with |x| <= 3 and scales <= 3 every partial sum is
+    # m/8 with |m| <= 72, exactly representable in bf16 (8 significant bits) and in f32
+    gates = {2: [.5, .5], 4: [.5, .25, .125, .125], 6: [.25, .25, .125, .125, .125, .125],
+             8: [.125] * 8}[k]
+    gates = np.array(gates)
+    w = np.tile(gates, (T, 1)).astype(np.float32)
+    x = wl.integer_valued_rows(T, d, seed=3, lo=-3, hi=3)
+    scale = (np.arange(E) % 3 + 1).astype(np.float64)
+
+    layer = OccultLayer(T, d, 64, E, 0, k, D, dtype, expert_pos=pos, with_ffn=False)
+    x_d = to_dev(x, dtype, dev)
+    layer.make_plan(torch.from_numpy(ids).to(dev), torch.from_numpy(w).to(dev))
+    layer.dispatch(x_d)
+    torch.cuda.synchronize()
+    tabs = layer.tables()
+    trace = occult_ref.moe_forward(x, ids, w.astype(np.float64), pos_arr, D, bypass_scale=scale,
+                                   acc=np.float64)
+    n_sfd = trace.n_sfd
+    # dispatch: the send buffer, bit for bit
+    assert np.array_equal(layer.sfd_x[:n_sfd].float().cpu().numpy(), trace.x_sfd)
+
+    # test scaffolding in place of the expert network: epd_y[q] = scale[expert of q] * sfd_x[source]
+    exp_off = tabs["exp_offset"].cpu().numpy()
+    pos_expert = tabs["pos_expert"].cpu().numpy()
+    row_scale = np.repeat(scale[pos_expert], np.diff(exp_off)).astype(np.float32)
+    src = tabs["epd_sfd_row"].long()
+    epd_y = (layer.sfd_x[src].float() * torch.from_numpy(row_scale).to(dev)[:, None]).to(layer.tdtype)
+    layer.combine(epd_y.contiguous())
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.sfd_y[:n_sfd].float().cpu().numpy(), trace.y_sfd)
+    assert np.array_equal(layer.y.float().cpu().numpy(), trace.y)
+
+
+@pytest.mark.parametrize("dtype,S", [("bf16", 0), ("bf16", 1), ("f32", 0), ("f32", 1)])
+def test_combine_random_values_against_two_stage_oracle(dtype, S):
+    say(f"combine random case {dtype} S={S}")
+    dev = require_gpu()
+    E, D, k, T, d = 32, 4, 6, 900, 1024
+    G = E // D
+    rng = np.random.default_rng(5)
+    lg = wl.random_logits(T, E, seed=9)
+    pos = wl.random_placement(E, D, seed=1)
+    ids, w = routing.route(lg, k, D, pos)
+    w32 = w.astype(np.float32)
+    layer = OccultLayer(T, d, 64, E, S, k, D, dtype, expert_pos=pos, with_ffn=False)
+    layer.make_plan(torch.from_numpy(ids).to(dev), torch.from_numpy(w32).to(dev))
+    torch.cuda.synchronize()
+    epd_y = rng.standard_normal((T * k, d)).astype(np.float32)
+    y_sh = rng.standard_normal((T, d)).astype(np.float32) if S else None
+    if dtype == "bf16":
+        epd_y = wl.round_to_bf16(epd_y)
+        y_sh = wl.round_to_bf16(y_sh) if S else None
+    layer.y_shared = to_dev(y_sh, dtype, dev) if S else None
+    layer.combine(to_dev(epd_y, dtype, dev))
+    torch.cuda.synchronize()
+    # oracle arithmetic of the two stages (Sec. 3.1) on the oracle's own re-index matrices:
+    # weight modulation + serial merge over local experts per device, payload rounding, Combine
+    trace = occult_ref.moe_forward(np.zeros((T, 1)), ids, w32.astype(np.float64), pos, D)
+    n_sfd = trace.n_sfd
+    off = np.concatenate([[0], np.cumsum(trace.dev_count)])
+    sfd_ref = np.zeros((n_sfd, d))
+    base = 0
+    for j in range(D):
+        b1, bw = trace.brim_1[j], trace.brim_w[j]
+        n_loc = int((b1 >= 0).sum())
+        x_epd = occult_ref.weight_modulate(epd_y[base:base + n_loc].astype(np.float64), b1, bw)
+        seg = np.zeros((b1.shape[1], d))
+        for e in range(G):
+            present = b1[e] >= 0
+            seg[present] += x_epd[b1[e][present]]
+        sfd_ref[off[j]:off[j + 1]] = seg
+        base += n_loc
+    got_sfd = layer.sfd_y[:n_sfd].float().cpu().numpy()
+    sfd_payload = wl.round_to_bf16(sfd_ref.astype(np.float32)) if dtype == "bf16" else sfd_ref
+    y_ref = occult_ref.combine(sfd_payload.astype(np.float64), trace.brim_0, np.float64)
+    if S:
+        y_ref += y_sh
+    got_y = layer.y.float().cpu().numpy()
+    if dtype == "bf16":
+        mx, mean = bf16_errors(got_sfd, sfd_ref)
+        assert mx <= 2e-2 and mean <= 2e-3, (mx, mean)
+        mx, mean = bf16_errors(got_y, y_ref)
+        assert mx <= 4e-2 and mean <= 4e-3, (mx, mean)   # |y| ~ 2-8 here: one bf16 ulp is 3e-2
+    else:
+        assert f32_rel_error(got_sfd, sfd_ref) <= 1e-5
+        assert f32_rel_error(got_y, y_ref) <= 1e-5

@@ -1,0 +1,162 @@
+"""GPU parity for occult_expert_ffn and the whole hot path (route -> plan -> dispatch -> expert
+FFN -> combine) against the textbook layer O-std in float64.
+
+Bars (from the build's baseline file): f32 outputs within max-rel 1e-5 (relative to
+max(|o|, rms(o)) so that entries near zero do not dominate), bf16 outputs within max-abs 2e-2
+and mean-abs 2e-3 of the oracle's exactly accumulated result.
+"""
+import numpy as np
+import pytest
+import torch
+
+from inputs import workloads as wl
+from oracle import moe_std, occult_ref, routing
+from paper_2505_13345_amd.layer import OccultLayer
+from tests.helpers import bf16_errors, f32_rel_error, require_gpu, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_layer(shape, wk, pos=None):
+    dev = require_gpu()
+    layer = OccultLayer(shape.T, shape.d, shape.f, shape.E, shape.S, shape.k, shape.D, shape.dtype,
+                        shape.n_d, shape.prune_mode, shape.renorm, pos)
+    x = to_dev(wk.x, shape.dtype, dev)
+    wg, wu, wd = (to_dev(a, shape.dtype, dev) for a in (wk.w_gate, wk.w_up, wk.w_down))
+    y = layer.forward(torch.from_numpy(wk.logits).to(dev), x, wg, wu, wd)
+    torch.cuda.synchronize()
+    return layer, y.float().cpu().numpy()
+
+
+SMALL = [
+    # name, T, d, f, E, S, k, D, dtype   (several tiles and ragged tails in M, N and groups)
+    ("f32_a", 300, 96, 80, 8, 0, 2, 4, "f32"),
+    ("f32_shared", 130, 128, 256, 16, 2, 4, 4, "f32"),
+    ("bf16_a", 700, 256, 192, 8, 0, 2, 4, "bf16"),
+    ("bf16_shared", 333, 512, 320, 12, 2, 3, 3, "bf16"),
+    ("bf16_one_row_experts", 9, 128, 64, 16, 1, 2, 8, "bf16"),
+    ("bf16_big_expert", 1500, 192, 448, 4, 0, 1, 2, "bf16"),
+]
+
+
+@pytest.mark.parametrize("name,T,d,f,E,S,k,D,dtype", SMALL)
+def test_small_layers_elementwise(name, T, d, f, E, S, k, D, dtype):
+    say(f"small layer {name}")
+    shape = wl.LayerShape(name, T=T, d=d, f=f, E=E, S=S, k=k, D=D, dtype=dtype,
+                          components=4 if dtype == "bf16" else 0)
+    wk = wl.make_workload(shape, seed=17)
+    pos = wl.random_placement(E, D, seed=2)
+    layer, y = _run_layer(shape, wk, pos)
+    ids, w = layer.ids.cpu().numpy(), layer.w.cpu().numpy().astype(np.float64)
+    ids_ref, _ = routing.route(wk.logits, k, D, pos)
+    assert np.array_equal(ids, ids_ref)
+    y_ref = moe_std.moe_layer(wk.x, ids, w, wk.w_gate, wk.w_up, wk.w_down, E, S)
+    # the deduplicated oracle reaches the same numbers (exactness), and gives the intermediates
+    tr = occult_ref.moe_forward(wk.x, ids, w, pos, D, wk.w_gate, wk.w_up, wk.w_down, S)
+    assert np.allclose(tr.y, y_ref, rtol=1e-9, atol=1e-11)
+    n_sfd = tr.n_sfd
+    sfd_y = layer.sfd_y[:n_sfd].float().cpu().numpy()
+    if dtype == "f32":
+        assert f32_rel_error(y, y_ref) <= 1e-5
+        assert f32_rel_error(sfd_y, tr.y_sfd) <= 1e-5
+    else:
+        mx, mean = bf16_errors(y, y_ref)
+        say(f"  y max-abs {mx:.3e} mean-abs {mean:.3e}")
+        assert mx <= 2e-2 and mean <= 2e-3
+        mx, mean = bf16_errors(sfd_y, tr.y_sfd)
+        assert mx <= 2e-2 and mean <= 2e-3
+
+
+def test_tiny_f32_config_full_layer():
+    shape = wl.CONFIGS["tiny_f32"]
+    wk = wl.make_workload(shape)
+    layer, y = _run_layer(shape, wk)
+    ids, w = layer.ids.cpu().numpy(), layer.w.cpu().numpy().astype(np.float64)
+    ids_ref, w_ref = routing.route(wk.logits, shape.k, shape.D)
+    assert np.array_equal(ids, ids_ref)
+    y_ref = moe_std.moe_layer(wk.x, ids_ref, w_ref, wk.w_gate, wk.w_up, wk.w_down, shape.E, 0)
+    err = f32_rel_error(y, y_ref)
+    say(f"tiny_f32 normalised max-rel {err:.3e}; plain max-rel "
+        f"{np.max(np.abs(y - y_ref) / np.maximum(np.abs(y_ref), 1e-30)):.3e}")
+    assert err <= 1e-5
+
+
+def test_decode_config_full_layer():
+    shape = wl.CONFIGS["decode_bf16"]
+    say("decode_bf16: generating")
+    wk = wl.make_workload(shape)
+    layer, y = _run_layer(shape, wk)
+    ids, w = layer.ids.cpu().numpy(), layer.w.cpu().numpy().astype(np.float64)
+    y_ref = moe_std.moe_layer(wk.x, ids, w, wk.w_gate, wk.w_up, wk.w_down, shape.E, shape.S)
+    mx, mean = bf16_errors(y, y_ref)
+    say(f"decode_bf16: y max-abs {mx:.3e} mean-abs {mean:.3e} |y|max {np.abs(y_ref).max():.2f}")
+    assert mx <= 2e-2 and mean <= 2e-3
+
+
+def _sampled_parity(name, n_sample=192, pos=None, wk=None):
+    shape = wl.CONFIGS[name]
+    if wk is None:
+        say(f"{name}: generating")
+        wk = wl.make_workload(shape)
+    say(f"{name}: running on GPU")
+    layer, y = _run_layer(shape, wk, pos)
+    ids, w = layer.ids.cpu().numpy(), layer.w.cpu().numpy().astype(np.float64)
+    ids_ref, _ = routing.route(wk.logits, shape.k, shape.D, pos, shape.n_d, shape.prune_mode, shape.renorm)
+    assert np.array_equal(ids, ids_ref)
+    rng = np.random.default_rng(123)
+    tokens = np.sort(rng.choice(shape.T, size=n_sample, replace=False))
+    tokens[0], tokens[-1] = 0, shape.T - 1
+    say(f"{name}: oracle on {n_sample} sampled tokens")
+    y_ref = moe_std.moe_layer(wk.x, ids, w, wk.w_gate, wk.w_up, wk.w_down, shape.E, shape.S, tokens=tokens)
+    mx, mean = bf16_errors(y[tokens], y_ref)
+    say(f"{name}: sampled y max-abs {mx:.3e} mean-abs {mean:.3e} |y|max {np.abs(y_ref).max():.2f}")
+    assert mx <= 2e-2 and mean <= 2e-3
+    # properties that hold at any size: every output finite, no row left unwritten
+    assert np.isfinite(y).all()
+    assert (np.abs(y).sum(axis=1) > 0).all()
+    return wk, layer, y
+
+
+def test_prefill_config_sampled_and_pruned_variant():
+    wk, layer, y = _sampled_parity("prefill_bf16")
+    st = layer.stats()
+    del layer
+    torch.cuda.empty_cache()
+    # same tensors with collaboration pruning to 2 devices
+    wk2, layer2, y2 = _sampled_parity("prefill_pruned_bf16", wk=wk)
+    st2 = layer2.stats()
+    assert st2.c_t <= 2.0 < st.c_t
+    diff = np.abs(y2.astype(np.float64) - y)
+    rel_fro = np.linalg.norm(y2.astype(np.float64) - y) / np.linalg.norm(y)
+    say(f"pruned vs unpruned: C_T {st.c_t:.3f} -> {st2.c_t:.3f}; bytes/token {st.bytes_occ / 16384:.0f} -> "
+        f"{st2.bytes_occ / 16384:.0f} (standard {st.bytes_std / 16384:.0f}); output diff max-abs "
+        f"{diff.max():.3f} mean-abs {diff.mean():.4f} rel-Frobenius {rel_fro:.3f}")
+    assert 0.0 < rel_fro < 1.0
+
+
+def test_large_config_sampled_with_greedy_placement():
+    from oracle import collaboration
+    from paper_2505_13345_amd import binding as B
+    shape = wl.CONFIGS["large_bf16"]
+    wk, layer, y = _sampled_parity("large_bf16", n_sample=128)
+    st = layer.stats()
+    dev = require_gpu()
+    C = torch.zeros((shape.E, shape.E), dtype=torch.int32, device=dev)
+    B.occult_coactivation(layer.cfg, layer.ids, C, False)
+    torch.cuda.synchronize()
+    C_host = C.cpu().numpy()
+    ids = layer.ids.cpu().numpy()
+    assert np.array_equal(C_host, collaboration.coactivation(ids, shape.E))
+    L, pos = B.occult_placement_greedy(C_host, shape.D)
+    L_ref, pos_ref = collaboration.greedy_placement(C_host, shape.D)
+    assert pos.tolist() == pos_ref.tolist()
+    del layer
+    torch.cuda.empty_cache()
+    wk, layer2, y2 = _sampled_parity("large_bf16", n_sample=128, pos=pos, wk=wk)
+    st2 = layer2.stats()
+    say(f"large: C_T contiguous {st.c_t:.3f} -> greedy {st2.c_t:.3f}; bytes/token "
+        f"{st.bytes_occ / shape.T:.0f} -> {st2.bytes_occ / shape.T:.0f} (standard {st.bytes_std / shape.T:.0f})")
+    assert st2.c_t < st.c_t
+    # placement never changes the layer output beyond rounding (exactness)
+    mx, mean = bf16_errors(y2, y)
+    assert mx <= 4e-2 and mean <= 2e-3
