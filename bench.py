@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+One step = one pass of the whole hot path over one batch of synthetic input already resident in
+HBM: occult_route -> occult_plan -> occult_dispatch -> occult_expert_ffn -> occult_combine ->
+occult_coactivation, enqueued back to back on one stream with no host synchronisation.
+Prints ONE JSON line.  `value` is tokens per second of the whole step; per-call times (HIP events
+on the launching stream, separate passes after the timed region), the dispatch+FFN+combine rate,
+roofline fractions and the simulated exchange bytes per token ride along in the same line.
+
+The default workload is the prefill-shaped layer (T = 2**14 tokens, E = 64, k = 8: the shape of
+the paper's Table 1 measurement, sharded over 8 simulated devices).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
+
+# HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs scaled by a copy kernel of known size; see profiles/.  None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def _event_time_ms(fn, reps):
+    import torch
+    start = torch.cuda.Event(enable_timing=True)
+    end = torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(reps):
+        fn()
+    end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) / reps
+
+
+def cpu_baseline(wk, shape, sample_tokens):
+    """The oracle as it stands (float64, numpy/BLAS) on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import moe_std, routing
+    n = min(sample_tokens, shape.T)
+    tokens = np.arange(n)
+    t0 = time.perf_counter()
+    ids, w = routing.route(wk.logits[:n], shape.k, shape.D, None, shape.n_d, shape.prune_mode, shape.renorm)
+    moe_std.moe_layer(wk.x[:n], ids, w, wk.w_gate, wk.w_up, wk.w_down, shape.E, shape.S, tokens=tokens)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {n} tokens of the workload through oracle routing + textbook MoE layer "
+                      f"(float64, numpy BLAS), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="prefill_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=16384)
+    ap.add_argument("--call-reps", type=int, default=10)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is one GPU's share of the layer; only --gpus 1 is supported "
+              "(devices of expert parallelism are simulated as expert groups on one GPU).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from inputs import workloads as wl
+    from paper_2505_13345_amd import binding as B
+    from paper_2505_13345_amd.layer import OccultLayer
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    shape = wl.CONFIGS[args.workload]
+    wk = wl.make_workload(shape)
+    tdt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+    es = 2 if shape.dtype == "bf16" else 4
+    layer = OccultLayer(shape.T, shape.d, shape.f, shape.E, shape.S, shape.k, shape.D, shape.dtype,
+                        shape.n_d, shape.prune_mode, shape.renorm, None)
+    logits = torch.from_numpy(wk.logits).to(dev)
+    x = torch.from_numpy(wk.x).to(dev).to(tdt)
+    wg, wu, wd = (torch.from_numpy(a).to(dev).to(tdt) for a in (wk.w_gate, wk.w_up, wk.w_down))
+    C = torch.zeros((shape.E, shape.E), dtype=torch.int32, device=dev)
+
+    def step():
+        layer.route(logits)
+        layer.make_plan()
+        layer.dispatch(x)
+        layer.expert_ffn(x, wg, wu, wd)
+        layer.combine()
+        B.occult_coactivation(layer.cfg, layer.ids, C, False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    st = layer.stats()
+
+    # per-call times: HIP events on the stream the kernels are launched on (torch's current stream)
+    r = args.call_reps
+    calls = {
+        "route": _event_time_ms(lambda: layer.route(logits), r),
+        "plan": _event_time_ms(lambda: layer.make_plan(), r),
+        "dispatch": _event_time_ms(lambda: layer.dispatch(x), r),
+        "expert_ffn": _event_time_ms(lambda: layer.expert_ffn(x, wg, wu, wd), r),
+        "combine": _event_time_ms(lambda: layer.combine(), r),
+        "coactivation": _event_time_ms(lambda: B.occult_coactivation(layer.cfg, layer.ids, C, False), r),
+    }
+    layer.cfg.ffn_phase = 1
+    calls["ffn_gemm1_swiglu"] = _event_time_ms(lambda: layer.expert_ffn(x, wg, wu, wd), r)
+    layer.cfg.ffn_phase = 2
+    calls["ffn_gemm2_down"] = _event_time_ms(lambda: layer.expert_ffn(x, wg, wu, wd), r)
+    layer.cfg.ffn_phase = 0
+
+    T, d, f, k, S = shape.T, shape.d, shape.f, shape.k, shape.S
+    row = d * es
+    n_sfd, n_epd = st.n_sfd, T * k
+    # algorithmic work per call
+    flops1 = 4.0 * d * f * (n_epd + S * T)          # gate + up projections
+    flops2 = 2.0 * d * f * (n_epd + S * T)          # down projection
+    bytes_dispatch = (T + n_sfd) * row              # read each token once, write one row per device
+    bytes_combine = (n_epd + n_sfd + T + (T if S else 0)) * row   # fused two-stage combine
+    tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12
+    gbs = lambda by, ms: by / (ms * 1e-3) / 1e9
+    rooflines = {
+        "ffn_gemm1_swiglu": {"bound": "mfma", "achieved": tf(flops1, calls["ffn_gemm1_swiglu"]),
+                             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"},
+        "ffn_gemm2_down": {"bound": "mfma", "achieved": tf(flops2, calls["ffn_gemm2_down"]),
+                           "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"},
+        "expert_ffn": {"bound": "mfma", "achieved": tf(flops1 + flops2, calls["expert_ffn"]),
+                       "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"},
+        "dispatch": {"bound": "hbm", "achieved": gbs(bytes_dispatch, calls["dispatch"]),
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s"},
+        "combine": {"bound": "hbm", "achieved": gbs(bytes_combine, calls["combine"]),
+                    "peak": PEAK_HBM_GBS, "unit": "GB/s"},
+    }
+    for v in rooflines.values():
+        v["frac"] = v["achieved"] / v["peak"]
+    dom = dict(rooflines["ffn_gemm1_swiglu"])
+    dom["kernel"] = "grouped_gemm_bf16<SWIGLU> (gate/up projections of occult_expert_ffn)"
+    dom["traffic"] = MEASURED_TRAFFIC.get(args.workload)
+
+    three = calls["dispatch"] + calls["expert_ffn"] + calls["combine"]
+    out = {
+        "metric": "MoE-layer tokens/sec (dispatch+FFN+combine)",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "d": d, "f": f, "E": shape.E, "S": S, "k": k,
+                   "D": shape.D, "n_d": shape.n_d, "step": "route+plan+dispatch+expert_ffn+combine+coactivation"},
+        "roofline": dom,
+        "calls_ms": calls,
+        "tokens_per_s_dispatch_ffn_combine": T / (three * 1e-3),
+        "rooflines": rooflines,
+        "exchange": {"c_t": st.c_t, "bytes_per_token_occult": st.bytes_occ / T,
+                     "bytes_per_token_standard": st.bytes_std / T,
+                     "saved_fraction": 1.0 - st.bytes_occ / st.bytes_std,
+                     "meta_bytes_per_token": st.bytes_meta / T},
+    }
+    if not args.no_cpu_baseline:
+        del layer
+        out["cpu_baseline"] = cpu_baseline(wk, shape, args.cpu_sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -71,7 +71,9 @@ typedef struct occult_cfg {
                          walking the unpruned top-k in descending score (Sec. 3.3 wording)  */
   int32_t renorm;     /* 1 = gates divided by their sum over the selected k                 */
   int32_t dtype;      /* OCCULT_F32 or OCCULT_BF16: element type of x, weights, sfd, epd, y  */
-  int32_t reserved;
+  int32_t ffn_phase;  /* occult_expert_ffn only: 0 = both products; 1 = only the first (gate/up
+                         projections + SwiGLU -> epd_h, h_shared); 2 = only the second (down
+                         projection -> epd_y, y_shared).  For pipelining and per-kernel timing.  */
   const int32_t* expert_pos; /* device ptr [E]: placement position of each expert
                                 (device = pos / G, slot = pos % G); NULL = contiguous, pos[e] = e */
 } occult_cfg_t;

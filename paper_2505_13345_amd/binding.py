@@ -34,7 +34,7 @@ class OccultError(RuntimeError):
 class occult_cfg_t(Structure):
     _fields_ = [("T", c_int32), ("d", c_int32), ("f", c_int32), ("E", c_int32), ("S", c_int32),
                 ("k", c_int32), ("D", c_int32), ("n_d", c_int32), ("prune_mode", c_int32),
-                ("renorm", c_int32), ("dtype", c_int32), ("reserved", c_int32),
+                ("renorm", c_int32), ("dtype", c_int32), ("ffn_phase", c_int32),
                 ("expert_pos", c_void_p)]
 
 

@@ -36,6 +36,7 @@ int check_cfg(const occult_cfg_t* cfg) {
                 "n_d=%d devices of %d experts cannot hold k=%d experts", c.n_d, c.E / c.D, c.k);
   }
   OCC_REQUIRE(c.renorm == 0 || c.renorm == 1, OCCULT_EINVAL, "renorm=%d must be 0 or 1", c.renorm);
+  OCC_REQUIRE(c.ffn_phase >= 0 && c.ffn_phase <= 2, OCCULT_EINVAL, "ffn_phase=%d must be 0, 1 or 2", c.ffn_phase);
   return OCCULT_OK;
 }
 

@@ -336,8 +336,11 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
   g1.C = epd_h; g1.ldc = c.f; g1.c_col0 = 0;
   g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.w_base = 0;
   g1.ngroups = c.E; g1.M = 0; g1.N = c.f; g1.K = c.d;
-  rc = launch_gemm(c, g1, true, n_epd, s);
-  if (rc) return rc;
+  const bool do1 = c.ffn_phase != 2, do2 = c.ffn_phase != 1;
+  if (do1) {
+    rc = launch_gemm(c, g1, true, n_epd, s);
+    if (rc) return rc;
+  }
 
   GemmArgs g2{};
   g2.A = epd_h; g2.lda = c.f; g2.a_rows = nullptr;
@@ -346,13 +349,15 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
   g2.C = epd_y; g2.ldc = c.d; g2.c_col0 = 0;
   g2.grp_offset = plan->exp_offset; g2.grp_widx = plan->pos_expert; g2.w_base = 0;
   g2.ngroups = c.E; g2.M = 0; g2.N = c.d; g2.K = c.f;
-  rc = launch_gemm(c, g2, false, n_epd, s);
-  if (rc) return rc;
+  if (do2) {
+    rc = launch_gemm(c, g2, false, n_epd, s);
+    if (rc) return rc;
+  }
 
   if (c.S > 0) {
     // shared experts: h_shared[t][s*f .. (s+1)*f) per shared expert, then one product whose K
     // dimension walks the S down-projection matrices
-    for (int sh = 0; sh < c.S; ++sh) {
+    for (int sh = 0; do1 && sh < c.S; ++sh) {
       GemmArgs a1{};
       a1.A = x; a1.lda = c.d; a1.a_rows = nullptr;
       a1.B = weights->w_gate; a1.B2 = weights->w_up;
@@ -370,8 +375,10 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
     a2.C = y_shared; a2.ldc = c.d; a2.c_col0 = 0;
     a2.grp_offset = nullptr; a2.grp_widx = nullptr; a2.w_base = c.E;
     a2.ngroups = 1; a2.M = c.T; a2.N = c.d; a2.K = c.S * c.f;
-    rc = launch_gemm(c, a2, false, c.T, s);
-    if (rc) return rc;
+    if (do2) {
+      rc = launch_gemm(c, a2, false, c.T, s);
+      if (rc) return rc;
+    }
   }
   return OCCULT_OK;
 }
