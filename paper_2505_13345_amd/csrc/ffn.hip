@@ -37,6 +37,7 @@ struct GemmArgs {
   int w_base;
   int ngroups;
   int M;                    // rows when grp_offset == NULL
+  int a_rows_total;         // rows of the A buffer that may be addressed (bounds 32-bit offsets)
   int N;                    // output columns (for SWIGLU: columns of h)
   int K;
 };
@@ -44,6 +45,33 @@ struct GemmArgs {
 struct TileInfo {
   int group, m0, rows, row_base;
 };
+
+// Workgroup id -> (m-tile, n-tile).  Workgroups are handed to the 8 XCDs round-robin and each XCD
+// has its own L2, so the tiles an XCD runs at the same time should share operands: XCD x gets
+// "chunks" x, x+8, ... of MC consecutive m-tiles times all n-tiles (about one tile per CU of the
+// XCD), so that an A tile is fetched into one L2 only and a B tile is reused MC times there.
+struct TileMap {
+  int mt, nt;
+};
+__device__ __forceinline__ TileMap map_tile(int n_tiles) {
+  const int mc = max(1, (32 + n_tiles / 2) / n_tiles);
+  const int per_chunk = mc * n_tiles;
+  const int b = blockIdx.x;
+  const int xcd = b & 7, slot = b >> 3;
+  const int chunk = (slot / per_chunk) * 8 + xcd;
+  const int within = slot % per_chunk;
+  TileMap tm;
+  tm.mt = chunk * mc + within / n_tiles;
+  tm.nt = within % n_tiles;
+  return tm;
+}
+// grid size covering m_tiles x n_tiles under map_tile (host)
+static long long mapped_grid(long long m_tiles, int n_tiles) {
+  const int mc = (32 + n_tiles / 2) / n_tiles > 1 ? (32 + n_tiles / 2) / n_tiles : 1;
+  long long chunks = (m_tiles + mc - 1) / mc;
+  chunks = (chunks + 7) / 8 * 8;
+  return chunks * mc * n_tiles;
+}
 
 // Which group and row block does m-tile `mt` fall in?  Group g owns ceil(rows_g / BM) tiles.
 // Executed by every thread of the first wave; result through LDS.  group = -1: past the end.
@@ -93,10 +121,11 @@ __device__ __forceinline__ TileInfo find_tile(const GemmArgs& a, int mt, TileInf
 }
 
 // ------------------------------------------------------------------------------------------
-// bf16 MFMA kernel.  Block = 256 threads = 4 waves (2 x 2), block tile 128 x 128 x 64,
+// bf16 MFMA kernel, small tile (few rows per expert: decode-shaped layers).  Block = 256 threads = 4 waves (2 x 2), block tile 128 x 128 x 64,
 // wave tile 64 x 64 = 2 x 2 MFMA tiles of 32 x 32.  With SWIGLU the 128 B-rows of a tile are
 // [gate n0..n0+31 | up n0..n0+31 | gate n0+32..n0+63 | up n0+32..n0+63], so the two MFMA
 // columns of a wave hold gate and up of the same 32 output columns.
+namespace small {
 constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int LDS_STRIDE = BK + 8;   // 144-byte rows: 16-byte reads of 8 consecutive rows hit 8 distinct bank groups
 
@@ -108,8 +137,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 
   constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
   const int n_tiles = (a.N + BN_OUT - 1) / BN_OUT;
-  const int mt = blockIdx.x / n_tiles;
-  const int n0 = (blockIdx.x % n_tiles) * BN_OUT;
+  const TileMap tm = map_tile(n_tiles);
+  const int mt = tm.mt;
+  const int n0 = tm.nt * BN_OUT;
   const TileInfo ti = find_tile<BM>(a, mt, &s_info);
   if (ti.group < 0) return;
 
@@ -220,6 +250,238 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     }
   }
 }
+}  // namespace small
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel, main variant (prefill-shaped layers).  Block = 256 threads = 4 waves (2 x 2),
+// block tile 256 x 256 x 64, wave tile 128 x 128 = 4 x 4 MFMA tiles of 32 x 32 (256 accumulator
+// registers per lane, one wave per SIMD).
+//
+// Global -> LDS.  Operand tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4: no VGPR staging, no ds_write), double buffered: while tile kt is
+// multiplied, tile kt+1 lands in the other stage.  The loads are issued from inline assembly
+// (wave-uniform base in SGPRs + a 32-bit per-lane offset that is constant over K, so advancing K
+// costs two scalar adds) and waited for with an explicit vmcnt: the compiler's own wait insertion
+// treats an LDS-directed load as a FLAT access and could only wait for all outstanding loads at
+// every LDS read.  One such load writes 64 lanes x 16 bytes contiguously = 8 rows of 128 bytes,
+// so rows cannot be padded; bank conflicts of the 16-byte fragment reads are avoided by an XOR
+// swizzle instead: chunk c of row r lives at slot c ^ ((r >> 1) & 7), realised by the loading
+// lane's choice of global chunk.  (LDS has 64 banks = 256 bytes per clock: two 128-byte rows share
+// a bank line, so 16 consecutive rows x one chunk must cover the 16 slots of a line.)
+//
+// Schedule.  With one wave per SIMD nothing hides an instruction clump, so the K loop is written
+// as groups of {2 MFMAs, 1 LDS fragment read for the next K step, 1 tile load} pinned in source
+// order: the matrix pipe keeps running while the other pipes are fed.  No branch sits inside the
+// loop (each would make the register allocator shuffle the 256 accumulators).
+//
+// Epilogue.  The MFMA operands are swapped (weights as the row operand), so a lane holds 4
+// consecutive output columns of one row; results are staged through LDS (free after the K loop)
+// as bf16 and leave as 16-byte row-contiguous stores.  With SWIGLU the 128 B-rows of a wave's
+// half tile are [gate c..c+31 | up c..c+31 | gate c+32..c+63 | up c+32..c+63], so MFMA row blocks
+// (0,1) and (2,3) pair gate with up and the activation is applied in registers.
+namespace t256 {
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int A_BYTES = BM * BK * 2;             // 32 KiB
+constexpr int STAGE_BYTES = 2 * A_BYTES;         // 64 KiB: A tile then B tile
+constexpr int EPI_STRIDE = 128 * 2 + 16;         // staged output row of a wave: 128 bf16 + pad
+constexpr int EPI_BYTES = 4 * 128 * EPI_STRIDE;  // four waves x 128 rows
+constexpr int SMEM_BYTES = EPI_BYTES > 2 * STAGE_BYTES ? EPI_BYTES : 2 * STAGE_BYTES;
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+// 64 lanes x 16 bytes from global addresses base + off (base wave-uniform, off per lane, bytes)
+// to LDS [lds, lds + 1024), asynchronously; completion is counted by vmcnt
+__device__ __forceinline__ void load_to_lds_16(const char* base, unsigned off, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(off), "s"(base)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
+  __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
+  __shared__ TileInfo s_info;
+
+  constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+  const int n_tiles = (a.N + BN_OUT - 1) / BN_OUT;
+  const TileMap tm = map_tile(n_tiles);
+  const int n0 = tm.nt * BN_OUT;
+  const TileInfo ti = find_tile<BM>(a, tm.mt, &s_info);
+  if (ti.group < 0) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const long long widx = a.grp_widx ? a.grp_widx[ti.group] : (a.w_base + ti.group);
+
+  // loader role: load i (0..7) of this wave fills tile rows (wave*8 + i)*8 .. +7 of A and of B;
+  // lane -> row lane/8, slot lane%8
+  unsigned a_off[8], b_off[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = (wave * 8 + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+    int lr = ti.m0 + r;
+    if (lr >= ti.rows) lr = ti.rows - 1;   // rows past the group are computed and dropped
+    const int logical = ti.row_base + lr;
+    const long long src = a.a_rows ? a.a_rows[logical] : logical;
+    a_off[i] = (unsigned)((src * a.lda + chunk * 8) * 2);
+    int ncol;
+    if (SWIGLU) {
+      const int half = r >> 7, q = (r & 127) >> 5, within = r & 31;
+      ncol = n0 + half * 64 + (q >> 1) * 32 + within;   // q odd -> up matrix: loads 4..7 of every wave
+    } else {
+      ncol = n0 + r;
+    }
+    if (ncol >= a.N) ncol = a.N - 1;
+    b_off[i] = (unsigned)(((long long)ncol * a.ldb + chunk * 8) * 2);
+  }
+  const char* a_base = static_cast<const char*>(a.A);
+  const char* w_lo = static_cast<const char*>(a.B) + widx * a.b_group_stride * 2;                    // loads 0..3
+  const char* w_hi = SWIGLU ? static_cast<const char*>(a.B2) + widx * a.b_group_stride * 2 : w_lo;   // loads 4..7
+  const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+  const unsigned lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * 8192);
+
+  // fragment read offsets inside a 32-row block for the four 16-wide K steps of a tile
+  int foff[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    foff[kk] = (lane & 31) * 128 + (((2 * kk + (lane >> 5)) ^ ((lane >> 1) & 7)) * 16);
+
+  f32x16 acc[4][4];   // [weight-row block ni][token-row block mi]
+#pragma unroll
+  for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.0f;
+
+  const int nk = a.K / BK;
+  const int last = nk - 1;
+
+  // prologue: tile 0 -> stage 0
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    load_to_lds_16(a_base, a_off[i], lds_w + i * 1024);
+    load_to_lds_16(i < 4 ? w_lo : w_hi, b_off[i], lds_w + A_BYTES + i * 1024);
+  }
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // this wave's loads of tile kt have landed and its fragment reads of tile kt-1 are done;
+    // then the same for every wave of the block
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+    const int stage = kt & 1;
+    const char* As = smem + stage * STAGE_BYTES + wm * 128 * 128;
+    const char* Bs = smem + stage * STAGE_BYTES + A_BYTES + wn * 128 * 128;
+    // next tile (past the end: the final tile again, into the stage nobody reads any more; keeps
+    // the loop free of branches)
+    const int kn = kt + 1 < nk ? kt + 1 : last;
+    const int k0n = kn * BK;
+    const int seg = k0n / a.kseg;   // which weight matrix along K (shared down projection)
+    const char* a_next = a_base + (long long)k0n * 2;
+    const long long kb = ((long long)seg * a.b_group_stride + (k0n - seg * a.kseg)) * 2;
+    const char* lo_next = w_lo + kb;
+    const char* hi_next = w_hi + kb;
+    const unsigned lds_next = lds_w + (stage ^ 1) * STAGE_BYTES;
+
+    bf16x8 fa[2][4], fb[2][4];
+    auto read_frag = [&](int set, int kk, int idx) {   // idx 0..3: token rows, 4..7: weight rows
+      if (idx < 4)
+        fa[set][idx] = *reinterpret_cast<const bf16x8*>(As + idx * 32 * 128 + foff[kk]);
+      else
+        fb[set][idx - 4] = *reinterpret_cast<const bf16x8*>(Bs + (idx - 4) * 32 * 128 + foff[kk]);
+    };
+    auto mfma_pair = [&](int set, int g) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int t = 2 * g + q, ni = t >> 2, mi = t & 3;
+        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][ni], fa[set][mi], acc[ni][mi], 0, 0, 0);
+      }
+    };
+
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx) read_frag(0, 0, idx);
+    __builtin_amdgcn_sched_barrier(0);
+    // K step 0: A loads of the next tile, fragments of step 1
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      load_to_lds_16(a_next, a_off[g], lds_next + g * 1024);
+      read_frag(1, 1, g);
+      mfma_pair(0, g);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // K step 1: B loads of the next tile, fragments of step 2
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      load_to_lds_16(g < 4 ? lo_next : hi_next, b_off[g], lds_next + A_BYTES + g * 1024);
+      read_frag(0, 2, g);
+      mfma_pair(1, g);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // K step 2: fragments of step 3
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      read_frag(1, 3, g);
+      mfma_pair(0, g);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // K step 3
+#pragma unroll
+    for (int g = 0; g < 8; ++g) mfma_pair(1, g);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // every load has landed and every wave has finished reading the stages: LDS is free for the epilogue
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+
+  // epilogue.  acc[ni][mi] element r of lane l: output row (token) mi*32 + l%32, output column
+  // ni*32 + (r/4)*8 + (l/32)*4 + r%4 of the wave tile: 4 consecutive columns per register quad.
+  char* stg = smem + wave * (128 * EPI_STRIDE);   // this wave's staging area, [128 rows][EPI_STRIDE]
+  constexpr int W_COLS = SWIGLU ? 64 : 128;       // output columns of a wave tile
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    char* srow = stg + (mi * 32 + (lane & 31)) * EPI_STRIDE;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (SWIGLU) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+          float h[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float g = acc[2 * p][mi][q * 4 + e], u = acc[2 * p + 1][mi][q * 4 + e];
+            h[e] = g / (1.0f + __expf(-g)) * u;
+          }
+          uint2 v;
+          v.x = pack_bf16(h[0], h[1]);
+          v.y = pack_bf16(h[2], h[3]);
+          *reinterpret_cast<uint2*>(srow + (p * 32 + q * 8 + (lane >> 5) * 4) * 2) = v;
+        }
+      } else {
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+          uint2 v;
+          v.x = pack_bf16(acc[ni][mi][q * 4 + 0], acc[ni][mi][q * 4 + 1]);
+          v.y = pack_bf16(acc[ni][mi][q * 4 + 2], acc[ni][mi][q * 4 + 3]);
+          *reinterpret_cast<uint2*>(srow + (ni * 32 + q * 8 + (lane >> 5) * 4) * 2) = v;
+        }
+      }
+    }
+  }
+  // same wave reads back what it wrote: 16 bytes per lane along rows, row-contiguous global stores
+  constexpr int CHUNKS = W_COLS / 8;              // 16-byte chunks per staged row
+  constexpr int ROWS_PER_IT = 64 / CHUNKS;        // rows covered by one wave-wide access
+  __bf16* C = static_cast<__bf16*>(a.C);
+  const int col0 = n0 + wn * W_COLS + (lane % CHUNKS) * 8;
+#pragma unroll 4
+  for (int it = 0; it < 128 / ROWS_PER_IT; ++it) {
+    const int rl = it * ROWS_PER_IT + lane / CHUNKS;          // row inside the wave tile
+    const int row = ti.m0 + wm * 128 + rl;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + rl * EPI_STRIDE + (lane % CHUNKS) * 16);
+    if (row < ti.rows && col0 < a.N)
+      *reinterpret_cast<u32x4*>(C + (long long)(ti.row_base + row) * a.ldc + a.c_col0 + col0) = v;
+  }
+}
+}  // namespace t256
 
 // ------------------------------------------------------------------------------------------
 // f32 kernel: 16 x 16 outputs per block, one output per thread, 16-wide K slices through LDS.
@@ -277,14 +539,25 @@ __global__ __launch_bounds__(FM * FN) void grouped_gemm_f32(const GemmArgs a) {
 static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
   if (total_rows == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
-    const int bn_out = swiglu ? BN / 2 : BN;
-    const long long m_tiles = (total_rows + BM - 1) / BM + (a.grp_offset ? a.ngroups : 0);
-    const long long blocks = m_tiles * ((a.N + bn_out - 1) / bn_out);
+    // rows per group decide the tile: 256-row tiles once groups average >= 192 rows
+    const int groups = a.grp_offset ? a.ngroups : 1;
+    // 256-row tiles once groups average >= 192 rows and every A byte offset fits 32 bits
+    const bool use_big = (long long)total_rows >= 192ll * groups &&
+                         (long long)a.a_rows_total * a.lda * 2 < (1ll << 32);
+    const int bm = use_big ? t256::BM : small::BM;
+    const int bn = use_big ? t256::BN : small::BN;
+    const int bn_out = swiglu ? bn / 2 : bn;
+    const long long m_tiles = (total_rows + bm - 1) / bm + (a.grp_offset ? a.ngroups : 0);
+    const long long blocks = mapped_grid(m_tiles, (a.N + bn_out - 1) / bn_out);
     OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
-    if (swiglu)
-      hipLaunchKernelGGL(grouped_gemm_bf16<true>, dim3((unsigned)blocks), dim3(256), 0, s, a);
-    else
-      hipLaunchKernelGGL(grouped_gemm_bf16<false>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    const dim3 grid((unsigned)blocks), block(256);
+    if (use_big) {
+      if (swiglu) hipLaunchKernelGGL(t256::grouped_gemm_bf16<true>, grid, block, 0, s, a);
+      else hipLaunchKernelGGL(t256::grouped_gemm_bf16<false>, grid, block, 0, s, a);
+    } else {
+      if (swiglu) hipLaunchKernelGGL(small::grouped_gemm_bf16<true>, grid, block, 0, s, a);
+      else hipLaunchKernelGGL(small::grouped_gemm_bf16<false>, grid, block, 0, s, a);
+    }
   } else {
     const long long m_tiles = (total_rows + FM - 1) / FM + (a.grp_offset ? a.ngroups : 0);
     const long long blocks = m_tiles * ((a.N + FN - 1) / FN);
@@ -320,8 +593,8 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
   OCC_REQUIRE(((size_t)c.d * es) % 16 == 0 && ((size_t)c.f * es) % 16 == 0, OCCULT_EALIGN,
               "rows of d=%d or f=%d elements are not multiples of 16 bytes", c.d, c.f);
   if (c.dtype == OCCULT_BF16)
-    OCC_REQUIRE(c.d % BK == 0 && c.f % BK == 0, OCCULT_ESHAPE,
-                "bf16 path needs d and f to be multiples of %d (d=%d, f=%d)", BK, c.d, c.f);
+    OCC_REQUIRE(c.d % 64 == 0 && c.f % 64 == 0, OCCULT_ESHAPE,
+                "bf16 path needs d and f to be multiples of 64 (d=%d, f=%d)", c.d, c.f);
   OCC_REQUIRE(aligned16(sfd_x) && aligned16(epd_h) && aligned16(epd_y) && aligned16(x) &&
                   aligned16(h_shared) && aligned16(y_shared) && aligned16(weights->w_gate) &&
                   aligned16(weights->w_up) && aligned16(weights->w_down),
@@ -336,6 +609,7 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
   g1.C = epd_h; g1.ldc = c.f; g1.c_col0 = 0;
   g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.w_base = 0;
   g1.ngroups = c.E; g1.M = 0; g1.N = c.f; g1.K = c.d;
+  g1.a_rows_total = sfd_rows_max(c);
   const bool do1 = c.ffn_phase != 2, do2 = c.ffn_phase != 1;
   if (do1) {
     rc = launch_gemm(c, g1, true, n_epd, s);
@@ -349,6 +623,7 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
   g2.C = epd_y; g2.ldc = c.d; g2.c_col0 = 0;
   g2.grp_offset = plan->exp_offset; g2.grp_widx = plan->pos_expert; g2.w_base = 0;
   g2.ngroups = c.E; g2.M = 0; g2.N = c.d; g2.K = c.f;
+  g2.a_rows_total = n_epd;
   if (do2) {
     rc = launch_gemm(c, g2, false, n_epd, s);
     if (rc) return rc;
@@ -364,7 +639,7 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
       a1.b_group_stride = (long long)c.f * c.d; a1.ldb = c.d; a1.kseg = c.d;
       a1.C = h_shared; a1.ldc = c.S * c.f; a1.c_col0 = sh * c.f;
       a1.grp_offset = nullptr; a1.grp_widx = nullptr; a1.w_base = c.E + sh;
-      a1.ngroups = 1; a1.M = c.T; a1.N = c.f; a1.K = c.d;
+      a1.ngroups = 1; a1.M = c.T; a1.N = c.f; a1.K = c.d; a1.a_rows_total = c.T;
       rc = launch_gemm(c, a1, true, c.T, s);
       if (rc) return rc;
     }
@@ -374,7 +649,7 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
     a2.b_group_stride = (long long)c.d * c.f; a2.ldb = c.f; a2.kseg = c.f;
     a2.C = y_shared; a2.ldc = c.d; a2.c_col0 = 0;
     a2.grp_offset = nullptr; a2.grp_widx = nullptr; a2.w_base = c.E;
-    a2.ngroups = 1; a2.M = c.T; a2.N = c.d; a2.K = c.S * c.f;
+    a2.ngroups = 1; a2.M = c.T; a2.N = c.d; a2.K = c.S * c.f; a2.a_rows_total = c.T;
     if (do2) {
       rc = launch_gemm(c, a2, false, c.T, s);
       if (rc) return rc;
