@@ -297,6 +297,13 @@ __device__ __forceinline__ void load_to_lds_16(const char* base, unsigned off, u
 }
 #pragma clang diagnostic pop
 
+// silu(g) * u with the hardware exp2 and reciprocal (about 1 ulp each: far inside bf16 rounding);
+// the IEEE division would cost more VALU time per tile than the epilogue's stores
+__device__ __forceinline__ float swiglu_fast(float g, float u) {
+  const float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);
+  return g * u * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
@@ -358,77 +365,86 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   const int nk = a.K / BK;
   const int last = nk - 1;
 
-  // prologue: tile 0 -> stage 0
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    load_to_lds_16(a_base, a_off[i], lds_w + i * 1024);
-    load_to_lds_16(i < 4 ? w_lo : w_hi, b_off[i], lds_w + A_BYTES + i * 1024);
-  }
-
-  for (int kt = 0; kt < nk; ++kt) {
-    // this wave's loads of tile kt have landed and its fragment reads of tile kt-1 are done;
-    // then the same for every wave of the block
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-
-    const int stage = kt & 1;
+  bf16x8 fa[2][4], fb[2][4];
+  // fragment idx 0..3: token-row blocks, 4..7: weight-row blocks, of K step kk of the tile in `stage`
+  auto read_frag = [&](int set, int stage, int kk, int idx) {
     const char* As = smem + stage * STAGE_BYTES + wm * 128 * 128;
     const char* Bs = smem + stage * STAGE_BYTES + A_BYTES + wn * 128 * 128;
-    // next tile (past the end: the final tile again, into the stage nobody reads any more; keeps
-    // the loop free of branches)
-    const int kn = kt + 1 < nk ? kt + 1 : last;
-    const int k0n = kn * BK;
-    const int seg = k0n / a.kseg;   // which weight matrix along K (shared down projection)
-    const char* a_next = a_base + (long long)k0n * 2;
-    const long long kb = ((long long)seg * a.b_group_stride + (k0n - seg * a.kseg)) * 2;
-    const char* lo_next = w_lo + kb;
-    const char* hi_next = w_hi + kb;
-    const unsigned lds_next = lds_w + (stage ^ 1) * STAGE_BYTES;
-
-    bf16x8 fa[2][4], fb[2][4];
-    auto read_frag = [&](int set, int kk, int idx) {   // idx 0..3: token rows, 4..7: weight rows
-      if (idx < 4)
-        fa[set][idx] = *reinterpret_cast<const bf16x8*>(As + idx * 32 * 128 + foff[kk]);
-      else
-        fb[set][idx - 4] = *reinterpret_cast<const bf16x8*>(Bs + (idx - 4) * 32 * 128 + foff[kk]);
-    };
-    auto mfma_pair = [&](int set, int g) {
+    if (idx < 4)
+      fa[set][idx] = *reinterpret_cast<const bf16x8*>(As + idx * 32 * 128 + foff[kk]);
+    else
+      fb[set][idx - 4] = *reinterpret_cast<const bf16x8*>(Bs + (idx - 4) * 32 * 128 + foff[kk]);
+  };
+  auto mfma_pair = [&](int set, int g) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int t = 2 * g + q, ni = t >> 2, mi = t & 3;
-        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][ni], fa[set][mi], acc[ni][mi], 0, 0, 0);
-      }
-    };
+    for (int q = 0; q < 2; ++q) {
+      const int t = 2 * g + q, ni = t >> 2, mi = t & 3;
+      acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][ni], fa[set][mi], acc[ni][mi], 0, 0, 0);
+    }
+  };
+  // load g (0..7: A rows, 8..15: B rows) of K tile kt into `stage`.  Past the end the final tile
+  // is fetched again into a stage nobody reads any more: keeps the loop free of branches.
+  auto load_part = [&](int kt, int stage, int g) {
+    const int kc = kt < nk ? kt : last;
+    const int k0 = kc * BK;
+    const unsigned lds = lds_w + stage * STAGE_BYTES;
+    if (g < 8) {
+      load_to_lds_16(a_base + (long long)k0 * 2, a_off[g], lds + g * 1024);
+    } else {
+      const int seg = k0 / a.kseg;   // which weight matrix along K (shared down projection)
+      const long long kb = ((long long)seg * a.b_group_stride + (k0 - seg * a.kseg)) * 2;
+      load_to_lds_16((g - 8 < 4 ? w_lo : w_hi) + kb, b_off[g - 8], lds + A_BYTES + (g - 8) * 1024);
+    }
+  };
 
+  // prologue: tile 0 -> stage 0, its first fragments, first half of tile 1 -> stage 1
 #pragma unroll
-    for (int idx = 0; idx < 8; ++idx) read_frag(0, 0, idx);
-    __builtin_amdgcn_sched_barrier(0);
-    // K step 0: A loads of the next tile, fragments of step 1
+  for (int g = 0; g < 16; ++g) load_part(0, 0, g);
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+  for (int idx = 0; idx < 8; ++idx) read_frag(0, 0, 0, idx);
+#pragma unroll
+  for (int g = 0; g < 8; ++g) load_part(1, 1, g);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // Steady state for tile kt in stage s: its step-0 fragments are in set 0, tile kt+1 is half
+  // issued.  The block-wide wait for tile kt+1 sits before the last K step, so that the barrier
+  // and the first fragment reads of tile kt+1 run under the 16 MFMAs of that step.
+  for (int kt = 0; kt < nk; ++kt) {
+    const int s = kt & 1;
+    // K step 0: second half (B) of tile kt+1, fragments of step 1
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-      load_to_lds_16(a_next, a_off[g], lds_next + g * 1024);
-      read_frag(1, 1, g);
+      load_part(kt + 1, s ^ 1, 8 + g);
+      read_frag(1, s, 1, g);
       mfma_pair(0, g);
       __builtin_amdgcn_sched_barrier(0);
     }
-    // K step 1: B loads of the next tile, fragments of step 2
+    // K step 1: fragments of step 2
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-      load_to_lds_16(g < 4 ? lo_next : hi_next, b_off[g], lds_next + A_BYTES + g * 1024);
-      read_frag(0, 2, g);
+      read_frag(0, s, 2, g);
       mfma_pair(1, g);
       __builtin_amdgcn_sched_barrier(0);
     }
     // K step 2: fragments of step 3
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-      read_frag(1, 3, g);
+      read_frag(1, s, 3, g);
       mfma_pair(0, g);
       __builtin_amdgcn_sched_barrier(0);
     }
-    // K step 3
+    // tile kt+1 has landed (this wave's loads, then every wave's), and every wave has issued and
+    // completed its last reads of stage s, which may therefore be refilled
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // K step 3: first half (A) of tile kt+2 -> stage s, step-0 fragments of tile kt+1
 #pragma unroll
-    for (int g = 0; g < 8; ++g) mfma_pair(1, g);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int g = 0; g < 8; ++g) {
+      load_part(kt + 2, s, g);
+      read_frag(0, s ^ 1, 0, g);
+      mfma_pair(1, g);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   // every load has landed and every wave has finished reading the stages: LDS is free for the epilogue
   asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -449,7 +465,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const float g = acc[2 * p][mi][q * 4 + e], u = acc[2 * p + 1][mi][q * 4 + e];
-            h[e] = g / (1.0f + __expf(-g)) * u;
+            h[e] = swiglu_fast(g, u);
           }
           uint2 v;
           v.x = pack_bf16(h[0], h[1]);
