@@ -165,6 +165,7 @@ __global__ __launch_bounds__(kScanThreads) void plan_scan(
   }
 }
 
+template <int KMAX>   // k <= KMAX: a token's positions and gates stay in registers
 __global__ __launch_bounds__(kTPB) void plan_fill(
     const int32_t* __restrict__ ids, const float* __restrict__ w, int T, int k, int E, int D, int G,
     int M1, const int32_t* __restrict__ expert_pos, const int32_t* __restrict__ blk_base,
@@ -178,19 +179,39 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
   const int t = blockIdx.x * kTPB + threadIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
+  // the token's selected positions and gates, kept in registers: looking a hit up by comparing
+  // against them costs a few ALU operations, re-reading ids / w per hit would cost a dependent
+  // memory round trip inside the rank loop
+  int tpos[KMAX];
+  float tgate[KMAX];
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    const bool live = (t < T) && (s < k);
+    tpos[s] = live ? s_pos[ids[(size_t)t * k + s]] : -1;
+    tgate[s] = live ? w[(size_t)t * k + s] : 0.0f;
+  }
   wave_counts(b, D, E, wave, lane, s_cnt);
   __syncthreads();
 
+  // per-wave counts -> first rank of each wave in each column: block base + waves before it
   const int C = D + E;
-  const int32_t* base = blk_base + (size_t)blockIdx.x * C;
+  for (int c = threadIdx.x; c < C; c += kTPB) {
+    int run = blk_base[(size_t)blockIdx.x * C + c];
+#pragma unroll
+    for (int wv = 0; wv < kWavesPerBlock; ++wv) {
+      const int n = s_cnt[wv][c];
+      s_cnt[wv][c] = run;
+      run += n;
+    }
+  }
+  __syncthreads();
+  const int* first = s_cnt[wave];
   const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 
   for (int j = 0; j < D; ++j) {
     const bool on = (b.dev >> j) & 1ull;
     const unsigned long long m = __ballot(on);
-    int before = 0;
-    for (int wv = 0; wv < wave; ++wv) before += s_cnt[wv][j];
-    const int r = on ? base[j] + before + __popcll(m & lt) : -1;
+    const int r = on ? first[j] + __popcll(m & lt) : -1;
     if (t < T) tok_sfd_row[(size_t)t * D + j] = r;
     if (on) sfd_token[r] = t;
 
@@ -200,13 +221,11 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
       const bool hit = has_pos(b, P);
       const unsigned long long me = __ballot(hit);
       if (me == 0ull) continue;   // wave-uniform
-      int pbefore = 0;
-      for (int wv = 0; wv < wave; ++wv) pbefore += s_cnt[wv][D + P];
       if (hit) {
-        const int q = base[D + P] + pbefore + __popcll(me & lt);
+        const int q = first[D + P] + __popcll(me & lt);
         float gate = 0.0f;
-        for (int s = 0; s < k; ++s)
-          if (s_pos[ids[(size_t)t * k + s]] == P) gate = w[(size_t)t * k + s];
+#pragma unroll
+        for (int s = 0; s < KMAX; ++s) gate = (tpos[s] == P) ? tgate[s] : gate;
         epd_sfd_row[q] = r;
         epd_gate[q] = gate;
         sfd_epd_rows[(size_t)r * M1 + filled] = q;
@@ -254,9 +273,14 @@ extern "C" int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const fl
                      p.counters);
   OCC_LAUNCH_CHECK("plan_scan");
   if (nblk > 0) {
-    hipLaunchKernelGGL(plan_fill, dim3(nblk), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G,
-                       merge_width(c), c.expert_pos, blk, p.tok_sfd_row, p.sfd_token, p.epd_sfd_row,
-                       p.epd_gate, p.sfd_epd_rows);
+#define OCC_PLAN_FILL(KM)                                                                              \
+  hipLaunchKernelGGL(plan_fill<KM>, dim3(nblk), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G,         \
+                     merge_width(c), c.expert_pos, blk, p.tok_sfd_row, p.sfd_token, p.epd_sfd_row,       \
+                     p.epd_gate, p.sfd_epd_rows)
+    if (c.k <= 8) OCC_PLAN_FILL(8);
+    else if (c.k <= 16) OCC_PLAN_FILL(16);
+    else OCC_PLAN_FILL(32);
+#undef OCC_PLAN_FILL
     OCC_LAUNCH_CHECK("plan_fill");
   }
   return OCCULT_OK;
