@@ -29,8 +29,9 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 
 # HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs scaled by a copy kernel of known size; see profiles/.  None = not measured.
-MEASURED_TRAFFIC = {}
+# WRITE_SIZE runs scaled by a copy kernel of known size (profiles/prefill_bf16_hbm_traffic.txt:
+# FETCH_SIZE 1041999 KiB x 2.0 + WRITE_SIZE 262144 KiB x 1.0).  Absent workload = not measured.
+MEASURED_TRAFFIC = {"prefill_bf16": (1041999 * 2.0 + 262144) * 1024}
 
 
 def _event_time_ms(fn, reps):
@@ -76,6 +77,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=16384)
     ap.add_argument("--call-reps", type=int, default=10)
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run an elementwise copy kernel over this many MiB (reads N, writes N bytes): "
+                         "the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is one GPU's share of the layer; only --gpus 1 is supported "
@@ -108,6 +112,13 @@ def main():
         layer.expert_ffn(x, wg, wu, wd)
         layer.combine()
         B.occult_coactivation(layer.cfg, layer.ids, C, False)
+
+    if args.copy_probe_mib > 0:
+        probe = torch.zeros(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.float32, device=dev)
+        for _ in range(3):
+            probe_out = probe + 1.0          # one kernel: reads and writes copy_probe_mib MiB
+        torch.cuda.synchronize()
+        del probe, probe_out
 
     for _ in range(args.warmup):
         step()
