@@ -58,9 +58,10 @@ __device__ __forceinline__ float bf16_lo(unsigned u) { return __uint_as_float(u 
 __device__ __forceinline__ float bf16_hi(unsigned u) { return __uint_as_float(u & 0xFFFF0000u); }
 // two floats -> two bf16 (round to nearest even) packed low | high << 16
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
-  const unsigned short a = __builtin_bit_cast(unsigned short, static_cast<__bf16>(lo));
-  const unsigned short b = __builtin_bit_cast(unsigned short, static_cast<__bf16>(hi));
-  return (unsigned)a | ((unsigned)b << 16);
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));   // one packed conversion
 }
 
 constexpr int kWave = 64;

@@ -53,18 +53,19 @@ struct TileInfo {
 struct TileMap {
   int mt, nt;
 };
-__device__ __forceinline__ TileMap map_tile(int n_tiles) {
+__device__ __forceinline__ TileMap map_tile_id(unsigned b, int n_tiles) {
   const int mc = max(1, (32 + n_tiles / 2) / n_tiles);
-  const int per_chunk = mc * n_tiles;
-  const int b = blockIdx.x;
-  const int xcd = b & 7, slot = b >> 3;
-  const int chunk = (slot / per_chunk) * 8 + xcd;
-  const int within = slot % per_chunk;
+  const unsigned per_chunk = mc * n_tiles;
+  const int xcd = (int)(b & 7);
+  const unsigned slot = b >> 3;
+  const int chunk = (int)(slot / per_chunk) * 8 + xcd;
+  const int within = (int)(slot % per_chunk);
   TileMap tm;
   tm.mt = chunk * mc + within / n_tiles;
   tm.nt = within % n_tiles;
   return tm;
 }
+__device__ __forceinline__ TileMap map_tile(int n_tiles) { return map_tile_id(blockIdx.x, n_tiles); }
 // grid size covering m_tiles x n_tiles under map_tile (host)
 static long long mapped_grid(long long m_tiles, int n_tiles) {
   const int mc = (32 + n_tiles / 2) / n_tiles > 1 ? (32 + n_tiles / 2) / n_tiles : 1;
@@ -255,11 +256,18 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel, main variant (prefill-shaped layers).  Block = 256 threads = 4 waves (2 x 2),
 // block tile 256 x 256 x 64, wave tile 128 x 128 = 4 x 4 MFMA tiles of 32 x 32 (256 accumulator
-// registers per lane, one wave per SIMD).
+// registers per lane, one wave per SIMD, one block per CU).
+//
+// Persistent blocks.  With one block per CU nothing overlaps a tile's fixed costs (finding its
+// group, gathering its row indices, the first operand loads, the store tail), so a block walks
+// output tiles blockIdx.x, + gridDim.x, ... of the XCD-aware order and treats them as one stream
+// of K tiles: the next output tile's group and row gather are fetched during the current K loop,
+// its first K tile is loaded during the current tile's last two K tiles, and its second one
+// during the epilogue.
 //
 // Global -> LDS.  Operand tiles go from global memory straight into LDS
-// (global_load_lds_dwordx4: no VGPR staging, no ds_write), double buffered: while tile kt is
-// multiplied, tile kt+1 lands in the other stage.  The loads are issued from inline assembly
+// (global_load_lds_dwordx4: no VGPR staging, no ds_write), double buffered: while K tile j is
+// multiplied, K tile j+1 lands in the other stage.  The loads are issued from inline assembly
 // (wave-uniform base in SGPRs + a 32-bit per-lane offset that is constant over K, so advancing K
 // costs two scalar adds) and waited for with an explicit vmcnt: the compiler's own wait insertion
 // treats an LDS-directed load as a FLAT access and could only wait for all outstanding loads at
@@ -269,23 +277,26 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 // lane's choice of global chunk.  (LDS has 64 banks = 256 bytes per clock: two 128-byte rows share
 // a bank line, so 16 consecutive rows x one chunk must cover the 16 slots of a line.)
 //
-// Schedule.  With one wave per SIMD nothing hides an instruction clump, so the K loop is written
-// as groups of {2 MFMAs, 1 LDS fragment read for the next K step, 1 tile load} pinned in source
-// order: the matrix pipe keeps running while the other pipes are fed.  No branch sits inside the
-// loop (each would make the register allocator shuffle the 256 accumulators).
+// Schedule.  With one wave per SIMD nothing hides an instruction clump, so a K step (16 MFMAs) is
+// written as 8 groups of {2 MFMAs, 1 LDS fragment read for the next K step, 1 tile load} pinned in
+// source order: the matrix pipe keeps running while the other pipes are fed.  The steps of a K
+// tile are rotated to 1, 2, wait, 3, 0': the block-wide wait for the next K tile sits before step
+// 3, so the barrier and the first fragment reads of that tile run under 16 MFMAs.  Step 0 of an
+// output tile multiplies into a zero constant, so accumulators are never cleared.  No branch sits
+// inside a K tile (each would make the register allocator shuffle the 256 accumulators).
 //
 // Epilogue.  The MFMA operands are swapped (weights as the row operand), so a lane holds 4
-// consecutive output columns of one row; results are staged through LDS (free after the K loop)
-// as bf16 and leave as 16-byte row-contiguous stores.  With SWIGLU the 128 B-rows of a wave's
-// half tile are [gate c..c+31 | up c..c+31 | gate c+32..c+63 | up c+32..c+63], so MFMA row blocks
-// (0,1) and (2,3) pair gate with up and the activation is applied in registers.
+// consecutive output columns of one row; results go as bf16 through the wave's own 8 KiB of the
+// idle stage (the region its own next loads will fill, so no block barrier is needed), 32 rows x
+// 64 columns at a time, and leave as 16-byte stores of whole 128-byte row segments.  With SWIGLU
+// the 128 B-rows of a wave's half tile are [gate c..c+31 | up c..c+31 | gate c+32..c+63 |
+// up c+32..c+63], so MFMA row blocks (0,1) and (2,3) pair gate with up and the activation is
+// applied in registers.
 namespace t256 {
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int A_BYTES = BM * BK * 2;             // 32 KiB
 constexpr int STAGE_BYTES = 2 * A_BYTES;         // 64 KiB: A tile then B tile
-constexpr int EPI_STRIDE = 128 * 2 + 16;         // staged output row of a wave: 128 bf16 + pad
-constexpr int EPI_BYTES = 4 * 128 * EPI_STRIDE;  // four waves x 128 rows
-constexpr int SMEM_BYTES = EPI_BYTES > 2 * STAGE_BYTES ? EPI_BYTES : 2 * STAGE_BYTES;
+constexpr int SMEM_BYTES = 2 * STAGE_BYTES;
 
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
@@ -295,6 +306,17 @@ __device__ __forceinline__ void load_to_lds_16(const char* base, unsigned off, u
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(off), "s"(base)
                : "memory", "m0");
 }
+// every load of this wave has landed and its LDS reads have returned; then the same for the block
+__device__ __forceinline__ void wait_all_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+#if defined(OCC_PROBE_NOVM)
+__device__ __forceinline__ void wait_loop() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+#elif defined(OCC_PROBE_NOBAR)
+__device__ __forceinline__ void wait_loop() { asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); }
+#else
+__device__ __forceinline__ void wait_loop() { wait_all_and_barrier(); }
+#endif
 #pragma clang diagnostic pop
 
 // silu(g) * u with the hardware exp2 and reciprocal (about 1 ulp each: far inside bf16 rounding);
@@ -304,66 +326,153 @@ __device__ __forceinline__ float swiglu_fast(float g, float u) {
   return g * u * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// One output tile before its row gather has come back.  All fields but raw are wave-uniform.
+struct Head {
+  int valid, m0, rows, row_base, n0, widx;
+  int raw[8];   // source rows of this lane's 8 A-tile rows
+};
+
+// which group and row block is m-tile mt?  s_tpre[g] = m-tiles of the groups before g (s_tpre[ngroups]
+// = all of them).  Every wave works this out for itself; the result is wave-uniform.
+// group = -1: past the last tile.
+__device__ __forceinline__ void locate(const GemmArgs& a, const int* s_goff, const int* s_tpre, int mt, int lane,
+                                       int& group, int& m0, int& rows, int& row_base) {
+  group = -1;
+  m0 = rows = row_base = 0;
+  if (a.grp_offset == nullptr) {
+    if ((long long)mt * BM < a.M) {
+      group = 0;
+      m0 = mt * BM;
+      rows = a.M;
+    }
+    return;
+  }
+  for (int c0 = 0; c0 < a.ngroups; c0 += 64) {
+    const int g = c0 + lane;
+    const bool mine = g < a.ngroups && mt >= s_tpre[g] && mt < s_tpre[g + 1];
+    const unsigned long long hit = __ballot(mine);
+    if (hit) {   // wave-uniform
+      group = c0 + __ffsll((long long)hit) - 1;
+      m0 = (mt - s_tpre[group]) * BM;
+      row_base = s_goff[group];
+      rows = s_goff[group + 1] - row_base;
+      return;
+    }
+  }
+}
+
+#ifdef OCC_TILE_TIMING
+__device__ long long g_tt[256 * 32 * 8];
+#define OCC_STAMP(j) do { if (tid == 0 && tile_no < 32) g_tt[(blockIdx.x * 32 + tile_no) * 8 + (j)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define OCC_STAMP(j) do {} while (0)
+#endif
+
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
-  __shared__ TileInfo s_info;
+  __shared__ int s_goff[OCCULT_MAX_E + 1];   // group row offsets
+  __shared__ int s_widx[OCCULT_MAX_E];       // weight matrix of each group
+  __shared__ int s_tpre[OCCULT_MAX_E + 1];   // m-tiles before each group
 
   constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
   const int n_tiles = (a.N + BN_OUT - 1) / BN_OUT;
-  const TileMap tm = map_tile(n_tiles);
-  const int n0 = tm.nt * BN_OUT;
-  const TileInfo ti = find_tile<BM>(a, tm.mt, &s_info);
-  if (ti.group < 0) return;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  const long long widx = a.grp_widx ? a.grp_widx[ti.group] : (a.w_base + ti.group);
+  if (a.grp_offset) {
+    for (int i = tid; i <= a.ngroups; i += 256) s_goff[i] = a.grp_offset[i];
+    for (int i = tid; i < a.ngroups; i += 256) s_widx[i] = a.grp_widx ? a.grp_widx[i] : a.w_base + i;
+    if (wave == 0) {   // exclusive scan of the groups' tile counts
+      int before = 0;
+      for (int c0 = 0; c0 < a.ngroups; c0 += 64) {
+        const int g = c0 + lane;
+        const int nt = g < a.ngroups ? (a.grp_offset[g + 1] - a.grp_offset[g] + BM - 1) / BM : 0;
+        int incl = nt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int v = __shfl_up(incl, o, 64);
+          if (lane >= o) incl += v;
+        }
+        if (g < a.ngroups) s_tpre[g] = before + incl - nt;
+        before += __shfl(incl, 63, 64);
+      }
+      if (lane == 0) s_tpre[a.ngroups] = before;
+    }
+  }
+  __syncthreads();
 
+  // tile L of the XCD-aware order; past the end (or with nothing left) the fields of `fallback`
+  // are kept, so that everything derived from a head stays addressable
+  auto head_of = [&](unsigned L, const Head* fallback) {
+    Head h;
+    const TileMap tm = map_tile_id(L, n_tiles);
+    int group;
+    locate(a, s_goff, s_tpre, tm.mt, lane, group, h.m0, h.rows, h.row_base);
+    h.valid = group >= 0;
+    h.n0 = tm.nt * BN_OUT;
+    h.widx = a.w_base;
+    if (h.valid) {
+      if (a.grp_offset) h.widx = s_widx[group];
+    } else if (fallback) {
+      h.m0 = fallback->m0; h.rows = fallback->rows; h.row_base = fallback->row_base;
+      h.n0 = fallback->n0; h.widx = fallback->widx;
+    }
+    h.widx = __builtin_amdgcn_readfirstlane(h.widx);
+    h.m0 = __builtin_amdgcn_readfirstlane(h.m0);
+    h.rows = __builtin_amdgcn_readfirstlane(h.rows);
+    h.row_base = __builtin_amdgcn_readfirstlane(h.row_base);
+    h.n0 = __builtin_amdgcn_readfirstlane(h.n0);
+    h.valid = __builtin_amdgcn_readfirstlane(h.valid);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = (wave * 8 + i) * 8 + (lane >> 3);
+      int lr = h.m0 + r;
+      if (lr >= h.rows) lr = h.rows - 1;   // rows past the group are computed and dropped
+      if (lr < 0) lr = 0;
+      const int logical = h.row_base + lr;
+      h.raw[i] = a.a_rows ? a.a_rows[logical] : logical;
+    }
+    return h;
+  };
   // loader role: load i (0..7) of this wave fills tile rows (wave*8 + i)*8 .. +7 of A and of B;
   // lane -> row lane/8, slot lane%8
-  unsigned a_off[8], b_off[8];
+  auto offsets_of = [&](const Head& h, unsigned (&ao)[8], unsigned (&bo)[8]) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int r = (wave * 8 + i) * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ ((r >> 1) & 7);
-    int lr = ti.m0 + r;
-    if (lr >= ti.rows) lr = ti.rows - 1;   // rows past the group are computed and dropped
-    const int logical = ti.row_base + lr;
-    const long long src = a.a_rows ? a.a_rows[logical] : logical;
-    a_off[i] = (unsigned)((src * a.lda + chunk * 8) * 2);
-    int ncol;
-    if (SWIGLU) {
-      const int half = r >> 7, q = (r & 127) >> 5, within = r & 31;
-      ncol = n0 + half * 64 + (q >> 1) * 32 + within;   // q odd -> up matrix: loads 4..7 of every wave
-    } else {
-      ncol = n0 + r;
+    for (int i = 0; i < 8; ++i) {
+      const int r = (wave * 8 + i) * 8 + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((r >> 1) & 7);
+      ao[i] = ((unsigned)h.raw[i] * (unsigned)a.lda + chunk * 8) * 2;   // host: A bytes < 2^32
+      int ncol;
+      if (SWIGLU) {
+        const int half = r >> 7, q = (r & 127) >> 5, within = r & 31;
+        ncol = h.n0 + half * 64 + (q >> 1) * 32 + within;   // q odd -> up matrix: loads 4..7 of every wave
+      } else {
+        ncol = h.n0 + r;
+      }
+      if (ncol >= a.N) ncol = a.N - 1;
+      bo[i] = (unsigned)(((long long)ncol * a.ldb + chunk * 8) * 2);
     }
-    if (ncol >= a.N) ncol = a.N - 1;
-    b_off[i] = (unsigned)(((long long)ncol * a.ldb + chunk * 8) * 2);
-  }
+  };
+
+  const unsigned stride = gridDim.x;   // host: tile ids + stride stay below 2^31
+  unsigned L = blockIdx.x;
+  Head hd = head_of(L, nullptr);
+  if (!hd.valid) return;   // uniform over the block; later tiles of this block are past the end too
+
   const char* a_base = static_cast<const char*>(a.A);
-  const char* w_lo = static_cast<const char*>(a.B) + widx * a.b_group_stride * 2;                    // loads 0..3
-  const char* w_hi = SWIGLU ? static_cast<const char*>(a.B2) + widx * a.b_group_stride * 2 : w_lo;   // loads 4..7
   const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
   const unsigned lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * 8192);
-
   // fragment read offsets inside a 32-row block for the four 16-wide K steps of a tile
   int foff[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
     foff[kk] = (lane & 31) * 128 + (((2 * kk + (lane >> 5)) ^ ((lane >> 1) & 7)) * 16);
+  const int nk = a.K / BK;   // host: >= 2
 
-  f32x16 acc[4][4];   // [weight-row block ni][token-row block mi]
-#pragma unroll
-  for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.0f;
-
-  const int nk = a.K / BK;
-  const int last = nk - 1;
+  unsigned a_off[8], b_off[8];
+  offsets_of(hd, a_off, b_off);
+  const char* w_lo = static_cast<const char*>(a.B) + (long long)hd.widx * a.b_group_stride * 2;   // loads 0..3
+  const char* w_hi = SWIGLU ? static_cast<const char*>(a.B2) + (long long)hd.widx * a.b_group_stride * 2 : w_lo;
 
   bf16x8 fa[2][4], fb[2][4];
   // fragment idx 0..3: token-row blocks, 4..7: weight-row blocks, of K step kk of the tile in `stage`
@@ -375,127 +484,253 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     else
       fb[set][idx - 4] = *reinterpret_cast<const bf16x8*>(Bs + (idx - 4) * 32 * 128 + foff[kk]);
   };
-  auto mfma_pair = [&](int set, int g) {
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int t = 2 * g + q, ni = t >> 2, mi = t & 3;
-      acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][ni], fa[set][mi], acc[ni][mi], 0, 0, 0);
-    }
+  // A rows / B rows of a K tile: load g (0..7) of this wave into `stage`
+  auto load_a = [&](const unsigned (&ao)[8], int ktile, int stage, int g) {
+    load_to_lds_16(a_base + (long long)ktile * (BK * 2), ao[g], lds_w + stage * STAGE_BYTES + g * 1024);
   };
-  // load g (0..7: A rows, 8..15: B rows) of K tile kt into `stage`.  Past the end the final tile
-  // is fetched again into a stage nobody reads any more: keeps the loop free of branches.
-  auto load_part = [&](int kt, int stage, int g) {
-    const int kc = kt < nk ? kt : last;
-    const int k0 = kc * BK;
-    const unsigned lds = lds_w + stage * STAGE_BYTES;
-    if (g < 8) {
-      load_to_lds_16(a_base + (long long)k0 * 2, a_off[g], lds + g * 1024);
-    } else {
-      const int seg = k0 / a.kseg;   // which weight matrix along K (shared down projection)
-      const long long kb = ((long long)seg * a.b_group_stride + (k0 - seg * a.kseg)) * 2;
-      load_to_lds_16((g - 8 < 4 ? w_lo : w_hi) + kb, b_off[g - 8], lds + A_BYTES + (g - 8) * 1024);
+  auto load_b = [&](const unsigned (&bo)[8], const char* lo, const char* hi, long long kb, int stage, int g) {
+    load_to_lds_16((g < 4 ? lo : hi) + kb, bo[g], lds_w + stage * STAGE_BYTES + A_BYTES + g * 1024);
+  };
+  // byte offset of K tile j inside a weight row; K > kseg walks consecutive weight matrices
+  // (down projection of the shared experts)
+  long long kb_next = 0;
+  int kin_next = 0;
+  auto kb_reset = [&]() { kb_next = 0; kin_next = 0; };
+  auto kb_advance = [&]() {
+    kb_next += BK * 2;
+    kin_next += BK;
+    if (kin_next >= a.kseg) {
+      kin_next = 0;
+      kb_next += (a.b_group_stride - a.kseg) * 2;
     }
   };
 
-  // prologue: tile 0 -> stage 0, its first fragments, first half of tile 1 -> stage 1
+  // prologue of the block: K tile 0 -> stage 0, its first fragments, A half of K tile 1 -> stage 1
+  int par = 0;   // stage holding K tile 0 of the current output tile
 #pragma unroll
-  for (int g = 0; g < 16; ++g) load_part(0, 0, g);
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  for (int g = 0; g < 8; ++g) load_a(a_off, 0, 0, g);
+#pragma unroll
+  for (int g = 0; g < 8; ++g) load_b(b_off, w_lo, w_hi, 0, 0, g);
+  wait_all_and_barrier();
 #pragma unroll
   for (int idx = 0; idx < 8; ++idx) read_frag(0, 0, 0, idx);
 #pragma unroll
-  for (int g = 0; g < 8; ++g) load_part(1, 1, g);
+  for (int g = 0; g < 8; ++g) load_a(a_off, 1, 1, g);
   __builtin_amdgcn_sched_barrier(0);
 
-  // Steady state for tile kt in stage s: its step-0 fragments are in set 0, tile kt+1 is half
-  // issued.  The block-wide wait for tile kt+1 sits before the last K step, so that the barrier
-  // and the first fragment reads of tile kt+1 run under the 16 MFMAs of that step.
-  for (int kt = 0; kt < nk; ++kt) {
-    const int s = kt & 1;
-    // K step 0: second half (B) of tile kt+1, fragments of step 1
-#pragma unroll
-    for (int g = 0; g < 8; ++g) {
-      load_part(kt + 1, s ^ 1, 8 + g);
-      read_frag(1, s, 1, g);
-      mfma_pair(0, g);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // K step 1: fragments of step 2
-#pragma unroll
-    for (int g = 0; g < 8; ++g) {
-      read_frag(0, s, 2, g);
-      mfma_pair(1, g);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // K step 2: fragments of step 3
-#pragma unroll
-    for (int g = 0; g < 8; ++g) {
-      read_frag(1, s, 3, g);
-      mfma_pair(0, g);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // tile kt+1 has landed (this wave's loads, then every wave's), and every wave has issued and
-    // completed its last reads of stage s, which may therefore be refilled
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    // K step 3: first half (A) of tile kt+2 -> stage s, step-0 fragments of tile kt+1
-#pragma unroll
-    for (int g = 0; g < 8; ++g) {
-      load_part(kt + 2, s, g);
-      read_frag(0, s ^ 1, 0, g);
-      mfma_pair(1, g);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
-  // every load has landed and every wave has finished reading the stages: LDS is free for the epilogue
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-
-  // epilogue.  acc[ni][mi] element r of lane l: output row (token) mi*32 + l%32, output column
-  // ni*32 + (r/4)*8 + (l/32)*4 + r%4 of the wave tile: 4 consecutive columns per register quad.
-  char* stg = smem + wave * (128 * EPI_STRIDE);   // this wave's staging area, [128 rows][EPI_STRIDE]
-  constexpr int W_COLS = SWIGLU ? 64 : 128;       // output columns of a wave tile
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi) {
-    char* srow = stg + (mi * 32 + (lane & 31)) * EPI_STRIDE;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (SWIGLU) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-          float h[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float g = acc[2 * p][mi][q * 4 + e], u = acc[2 * p + 1][mi][q * 4 + e];
-            h[e] = swiglu_fast(g, u);
-          }
-          uint2 v;
-          v.x = pack_bf16(h[0], h[1]);
-          v.y = pack_bf16(h[2], h[3]);
-          *reinterpret_cast<uint2*>(srow + (p * 32 + q * 8 + (lane >> 5) * 4) * 2) = v;
-        }
-      } else {
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-          uint2 v;
-          v.x = pack_bf16(acc[ni][mi][q * 4 + 0], acc[ni][mi][q * 4 + 1]);
-          v.y = pack_bf16(acc[ni][mi][q * 4 + 2], acc[ni][mi][q * 4 + 3]);
-          *reinterpret_cast<uint2*>(srow + (ni * 32 + q * 8 + (lane >> 5) * 4) * 2) = v;
-        }
-      }
-    }
-  }
-  // same wave reads back what it wrote: 16 bytes per lane along rows, row-contiguous global stores
-  constexpr int CHUNKS = W_COLS / 8;              // 16-byte chunks per staged row
-  constexpr int ROWS_PER_IT = 64 / CHUNKS;        // rows covered by one wave-wide access
+  const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   __bf16* C = static_cast<__bf16*>(a.C);
-  const int col0 = n0 + wn * W_COLS + (lane % CHUNKS) * 8;
-#pragma unroll 4
-  for (int it = 0; it < 128 / ROWS_PER_IT; ++it) {
-    const int rl = it * ROWS_PER_IT + lane / CHUNKS;          // row inside the wave tile
-    const int row = ti.m0 + wm * 128 + rl;
-    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + rl * EPI_STRIDE + (lane % CHUNKS) * 16);
-    if (row < ti.rows && col0 < a.N)
-      *reinterpret_cast<u32x4*>(C + (long long)(ti.row_base + row) * a.ldc + a.c_col0 + col0) = v;
+
+  int tile_no = 0;
+  while (true) {
+    // State here: K tile 0 of this output tile in stage par with its step-0 fragments in set 0;
+    // the A half of K tile 1 on its way into stage par ^ 1.
+    OCC_STAMP(0);
+    L += stride;
+    const Head hn = head_of(L, &hd);   // the next tile's row gather flies during this tile's K loop
+    kb_reset();
+    kb_advance();
+
+    f32x16 acc[4][4];   // [weight-row block ni][token-row block mi]
+    auto mfma_pair = [&](int set, int g) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int t = 2 * g + q, ni = t >> 2, mi = t & 3;
+        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][ni], fa[set][mi], acc[ni][mi], 0, 0, 0);
+      }
+    };
+    // K step 0 of the output tile: B half of K tile 1, fragments of step 1, products into zero
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      load_b(b_off, w_lo, w_hi, kb_next, par ^ 1, g);
+      read_frag(1, par, 1, g);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int t = 2 * g + q, ni = t >> 2, mi = t & 3;
+        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[0][ni], fa[0][mi], zero16, 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    kb_advance();
+    OCC_STAMP(1);
+
+    // steps 1 and 2 of K tile kt in stage s
+    auto steps_12 = [&](int s) {
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        read_frag(0, s, 2, g);
+        mfma_pair(1, g);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        read_frag(1, s, 3, g);
+        mfma_pair(0, g);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+
+    // K tiles 0 .. nk-3: steps 1, 2, wait for K tile kt+1, step 3, step 0 of K tile kt+1
+    for (int kt = 0; kt < nk - 2; ++kt) {
+      const int s = (par + kt) & 1;
+      steps_12(s);
+      // K tile kt+1 has landed (this wave's loads, then every wave's), and every wave has issued
+      // and completed its last reads of stage s, which may therefore be refilled
+      wait_loop();
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {   // step 3: A half of K tile kt+2 -> stage s, step-0 fragments of kt+1
+        load_a(a_off, kt + 2, s, g);
+        read_frag(0, s ^ 1, 0, g);
+        mfma_pair(1, g);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {   // step 0 of K tile kt+1: B half of K tile kt+2 -> stage s
+        load_b(b_off, w_lo, w_hi, kb_next, s, g);
+        read_frag(1, s ^ 1, 1, g);
+        mfma_pair(0, g);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      kb_advance();
+    }
+
+    // K tile nk-2: as above, but the stage it frees receives K tile 0 of the next output tile
+    OCC_STAMP(2);
+    const int s = (par + nk - 2) & 1, s1 = s ^ 1;
+    steps_12(s);
+    wait_all_and_barrier();
+    OCC_STAMP(3);
+    unsigned na_off[8], nb_off[8];
+    offsets_of(hn, na_off, nb_off);   // the gather has long landed: nothing is outstanding here
+    const char* nw_lo = static_cast<const char*>(a.B) + (long long)hn.widx * a.b_group_stride * 2;
+    const char* nw_hi = SWIGLU ? static_cast<const char*>(a.B2) + (long long)hn.widx * a.b_group_stride * 2 : nw_lo;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      load_a(na_off, 0, s, g);
+      read_frag(0, s1, 0, g);
+      mfma_pair(1, g);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      load_b(nb_off, nw_lo, nw_hi, 0, s, g);
+      read_frag(1, s1, 1, g);
+      mfma_pair(0, g);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // K tile nk-1 (stage s1): steps 1, 2; then the next tile's K tile 0 is complete in stage s and
+    // stage s1 is free: step 3 sends the A half of the next tile's K tile 1 there and reads the
+    // next tile's first fragments
+    OCC_STAMP(4);
+    steps_12(s1);
+    OCC_STAMP(5);
+    wait_all_and_barrier();
+    OCC_STAMP(6);
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+      load_a(na_off, 1, s1, g);
+      read_frag(0, s, 0, g);
+      mfma_pair(1, g);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // epilogue.  acc[ni][mi] element r of lane l: output row (token) mi*32 + l%32, output column
+    // ni*32 + (r/4)*8 + (l/32)*4 + r%4 of the wave tile: 4 consecutive columns per register quad.
+    // Chunk c = 32 rows x 64 output columns = 4 KiB (128-byte rows, 16-byte slots swizzled like
+    // the operand tiles), two buffers inside this wave's 8 KiB of stage s1's B region.
+    {
+      char* stg = smem + s1 * STAGE_BYTES + A_BYTES + wave * 8192;
+      constexpr int NCH = SWIGLU ? 4 : 8;
+      constexpr int W_COLS = SWIGLU ? 64 : 128;   // output columns of a wave tile
+      const int srow = lane & 31;
+      char* wr = stg + srow * 128 + (lane >> 5) * 8;
+      const int wsw = (srow >> 1) & 7;
+      const int rrow = lane >> 3, rch = lane & 7;
+      auto stage_chunk = [&](int c) {
+        char* buf = wr + (c & 1) * 4096;
+        const int mi = SWIGLU ? c : (c >> 1), h = SWIGLU ? 0 : (c & 1);
+#pragma unroll
+        for (int nn = 0; nn < 2; ++nn)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              if (SWIGLU)
+                v[e] = swiglu_fast(acc[2 * nn][mi][q * 4 + e], acc[2 * nn + 1][mi][q * 4 + e]);
+              else
+                v[e] = acc[2 * h + nn][mi][q * 4 + e];
+            }
+            uint2 pk;
+            pk.x = pack_bf16(v[0], v[1]);
+            pk.y = pack_bf16(v[2], v[3]);
+            *reinterpret_cast<uint2*>(buf + (((nn * 4 + q) ^ wsw) * 16)) = pk;
+          }
+      };
+      // Stores go through a buffer descriptor over the wave tile's valid rows, so rows past the
+      // group's end (and columns past N) are dropped by the hardware's range check: no branches.
+      const int rows_left = min(hd.rows - hd.m0 - wm * 128, 128);
+      const int col_w = hd.n0 + wn * W_COLS;   // first output column of the wave tile
+      const unsigned n_rec = rows_left > 0 ? (unsigned)((rows_left - 1) * a.ldc + W_COLS) * 2u : 0u;
+      const unsigned long long c_tile = reinterpret_cast<unsigned long long>(
+          C + (long long)(hd.row_base + hd.m0 + wm * 128) * a.ldc + a.c_col0 + col_w);
+      const unsigned long long c_tile_u =   // the descriptor has to sit in scalar registers
+          ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c_tile >> 32)) << 32) |
+          (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c_tile);
+      const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          reinterpret_cast<void*>(c_tile_u), 0, __builtin_amdgcn_readfirstlane((int)n_rec), 0x00020000);
+      u32x4 sv[4];
+      auto read_chunk = [&](int c) {
+        const char* buf = stg + (c & 1) * 4096;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int rl = it * 8 + rrow;   // row inside the 32-row chunk
+          sv[it] = *reinterpret_cast<const u32x4*>(buf + rl * 128 + ((rch ^ ((rl >> 1) & 7)) * 16));
+        }
+      };
+      auto store_chunk = [&](int c) {
+        const int mi = SWIGLU ? c : (c >> 1), h = SWIGLU ? 0 : (c & 1);
+        const int col = h * 64 + rch * 8;   // inside the wave tile
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int row = mi * 32 + it * 8 + rrow;
+          const unsigned off = col_w + col < a.N ? (unsigned)(row * a.ldc + col) * 2u : n_rec;
+          __builtin_amdgcn_raw_buffer_store_b128(sv[it], c_rsrc, (int)off, 0, 0);
+        }
+      };
+      // chunk c is converted and staged while the LDS reads of chunk c-1 are in flight
+      stage_chunk(0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int c = 1; c < NCH; ++c) {
+        read_chunk(c - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        stage_chunk(c);
+        __builtin_amdgcn_sched_barrier(0);
+        store_chunk(c - 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      read_chunk(NCH - 1);
+      store_chunk(NCH - 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    OCC_STAMP(7);
+    ++tile_no;
+    if (!hn.valid) break;   // uniform over the block
+    hd = hn;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a_off[i] = na_off[i];
+      b_off[i] = nb_off[i];
+    }
+    w_lo = nw_lo;
+    w_hi = nw_hi;
+    par = s;
   }
+  // the loads issued for a tile that does not exist must land before the block's LDS is released
+  wait_all_and_barrier();
 }
 }  // namespace t256
 
@@ -552,20 +787,46 @@ __global__ __launch_bounds__(FM * FN) void grouped_gemm_f32(const GemmArgs a) {
   }
 }
 
+// compute units of the current device (the persistent kernel runs one block on each), cached
+static int device_cu_count(int* out) {
+  static int cached[64];
+  int dev = 0;
+  OCC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64 || cached[dev] == 0) {
+    int n = 0;
+    OCC_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+    OCC_REQUIRE(n > 0, OCCULT_EHIP, "device reports %d compute units", n);
+    if (dev < 0 || dev >= 64) {
+      *out = n;
+      return OCCULT_OK;
+    }
+    cached[dev] = n;
+  }
+  *out = cached[dev];
+  return OCCULT_OK;
+}
+
 static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
   if (total_rows == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
-    // rows per group decide the tile: 256-row tiles once groups average >= 192 rows
     const int groups = a.grp_offset ? a.ngroups : 1;
-    // 256-row tiles once groups average >= 192 rows and every A byte offset fits 32 bits
+    // 256-row tiles once groups average >= 192 rows, every A byte offset fits 32 bits and there
+    // are at least two K tiles to pipeline
     const bool use_big = (long long)total_rows >= 192ll * groups &&
-                         (long long)a.a_rows_total * a.lda * 2 < (1ll << 32);
+                         (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK;
     const int bm = use_big ? t256::BM : small::BM;
     const int bn = use_big ? t256::BN : small::BN;
     const int bn_out = swiglu ? bn / 2 : bn;
     const long long m_tiles = (total_rows + bm - 1) / bm + (a.grp_offset ? a.ngroups : 0);
-    const long long blocks = mapped_grid(m_tiles, (a.N + bn_out - 1) / bn_out);
+    long long blocks = mapped_grid(m_tiles, (a.N + bn_out - 1) / bn_out);
     OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
+    if (use_big) {   // persistent: one block per CU, a multiple of 8 so a block keeps its XCD
+      int cus = 0;
+      const int rc = device_cu_count(&cus);
+      if (rc) return rc;
+      const long long resident = cus >= 8 ? cus / 8 * 8 : 8;
+      if (blocks > resident) blocks = resident;
+    }
     const dim3 grid((unsigned)blocks), block(256);
     if (use_big) {
       if (swiglu) hipLaunchKernelGGL(t256::grouped_gemm_bf16<true>, grid, block, 0, s, a);
@@ -590,6 +851,12 @@ static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, in
 }  // namespace occult
 
 using namespace occult;
+
+#ifdef OCC_TILE_TIMING
+extern "C" int occult_dbg_read(long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(t256::g_tt), sizeof(long long) * 256 * 32 * 8);
+}
+#endif
 
 extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
                                  const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
