@@ -310,13 +310,6 @@ __device__ __forceinline__ void load_to_lds_16(const char* base, unsigned off, u
 __device__ __forceinline__ void wait_all_and_barrier() {
   asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
-#if defined(OCC_PROBE_NOVM)
-__device__ __forceinline__ void wait_loop() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-#elif defined(OCC_PROBE_NOBAR)
-__device__ __forceinline__ void wait_loop() { asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)" ::: "memory"); }
-#else
-__device__ __forceinline__ void wait_loop() { wait_all_and_barrier(); }
-#endif
 #pragma clang diagnostic pop
 
 // silu(g) * u with the hardware exp2 and reciprocal (about 1 ulp each: far inside bf16 rounding);
@@ -361,12 +354,6 @@ __device__ __forceinline__ void locate(const GemmArgs& a, const int* s_goff, con
   }
 }
 
-#ifdef OCC_TILE_TIMING
-__device__ long long g_tt[256 * 32 * 8];
-#define OCC_STAMP(j) do { if (tid == 0 && tile_no < 32) g_tt[(blockIdx.x * 32 + tile_no) * 8 + (j)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define OCC_STAMP(j) do {} while (0)
-#endif
 
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
@@ -521,11 +508,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   __bf16* C = static_cast<__bf16*>(a.C);
 
-  int tile_no = 0;
   while (true) {
     // State here: K tile 0 of this output tile in stage par with its step-0 fragments in set 0;
     // the A half of K tile 1 on its way into stage par ^ 1.
-    OCC_STAMP(0);
     L += stride;
     const Head hn = head_of(L, &hd);   // the next tile's row gather flies during this tile's K loop
     kb_reset();
@@ -552,7 +537,6 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       __builtin_amdgcn_sched_barrier(0);
     }
     kb_advance();
-    OCC_STAMP(1);
 
     // steps 1 and 2 of K tile kt in stage s
     auto steps_12 = [&](int s) {
@@ -576,7 +560,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       steps_12(s);
       // K tile kt+1 has landed (this wave's loads, then every wave's), and every wave has issued
       // and completed its last reads of stage s, which may therefore be refilled
-      wait_loop();
+      wait_all_and_barrier();
 #pragma unroll
       for (int g = 0; g < 8; ++g) {   // step 3: A half of K tile kt+2 -> stage s, step-0 fragments of kt+1
         load_a(a_off, kt + 2, s, g);
@@ -595,11 +579,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     }
 
     // K tile nk-2: as above, but the stage it frees receives K tile 0 of the next output tile
-    OCC_STAMP(2);
     const int s = (par + nk - 2) & 1, s1 = s ^ 1;
     steps_12(s);
     wait_all_and_barrier();
-    OCC_STAMP(3);
     unsigned na_off[8], nb_off[8];
     offsets_of(hn, na_off, nb_off);   // the gather has long landed: nothing is outstanding here
     const char* nw_lo = static_cast<const char*>(a.B) + (long long)hn.widx * a.b_group_stride * 2;
@@ -622,11 +604,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     // K tile nk-1 (stage s1): steps 1, 2; then the next tile's K tile 0 is complete in stage s and
     // stage s1 is free: step 3 sends the A half of the next tile's K tile 1 there and reads the
     // next tile's first fragments
-    OCC_STAMP(4);
     steps_12(s1);
-    OCC_STAMP(5);
     wait_all_and_barrier();
-    OCC_STAMP(6);
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
       load_a(na_off, 1, s1, g);
@@ -715,9 +694,6 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       store_chunk(NCH - 1);
       __builtin_amdgcn_sched_barrier(0);
     }
-
-    OCC_STAMP(7);
-    ++tile_no;
     if (!hn.valid) break;   // uniform over the block
     hd = hn;
 #pragma unroll
@@ -852,11 +828,6 @@ static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, in
 
 using namespace occult;
 
-#ifdef OCC_TILE_TIMING
-extern "C" int occult_dbg_read(long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(t256::g_tt), sizeof(long long) * 256 * 32 * 8);
-}
-#endif
 
 extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
                                  const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
