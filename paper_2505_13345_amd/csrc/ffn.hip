@@ -31,8 +31,9 @@ struct GemmArgs {
   int kseg;                 // K elements held by one weight matrix; K > kseg walks consecutive matrices
   void* C;                  // output rows
   int ldc;                  // elements between C rows
-  int c_col0;               // first output column written
-  const int32_t* grp_offset;  // [ngroups+1] logical-row prefix per group, or NULL: one group of M rows
+  int c_col0;               // first output column written by group 0
+  int c_group_cols;         // group g writes from column c_col0 + g * c_group_cols
+  const int32_t* grp_offset;  // [ngroups+1] logical-row prefix per group, or NULL: every group takes rows [0, M)
   const int32_t* grp_widx;    // [ngroups] weight matrix of each group, or NULL: w_base + group
   int w_base;
   int ngroups;
@@ -45,6 +46,8 @@ struct GemmArgs {
 struct TileInfo {
   int group, m0, rows, row_base;
 };
+// first output column of a group
+__device__ __forceinline__ int group_col0(const GemmArgs& a, int group) { return a.c_col0 + group * a.c_group_cols; }
 
 // Workgroup id -> (m-tile, n-tile).  Workgroups are handed to the 8 XCDs round-robin and each XCD
 // has its own L2, so the tiles an XCD runs at the same time should share operands: XCD x gets
@@ -84,9 +87,10 @@ __device__ __forceinline__ TileInfo find_tile(const GemmArgs& a, int mt, TileInf
     ti.group = -1;
     ti.m0 = ti.rows = ti.row_base = 0;
     if (a.grp_offset == nullptr) {
-      if (mt * BM < a.M) {
-        ti.group = 0;
-        ti.m0 = mt * BM;
+      const int per_group = (a.M + BM - 1) / BM;
+      if (mt < per_group * a.ngroups) {
+        ti.group = mt / per_group;
+        ti.m0 = (mt % per_group) * BM;
         ti.rows = a.M;
       }
       if (lane == 0) *s_info = ti;
@@ -184,8 +188,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
 
   const int nk = a.K / BK;
-  u32x4 ga[4], gb[4];
-  auto load_global = [&](int kt) {
+  // two K tiles are in flight in registers while a third is multiplied out of LDS
+  u32x4 ga0[4], gb0[4], ga1[4], gb1[4];
+  auto load_global = [&](int kt, u32x4 (&ga)[4], u32x4 (&gb)[4]) {
     const int k0 = kt * BK;
     const int seg = k0 / a.kseg;                 // which weight matrix along K (shared down-proj)
     const long long boff = (long long)seg * a.b_group_stride + (k0 - seg * a.kseg);
@@ -195,9 +200,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       gb[i] = *reinterpret_cast<const u32x4*>(b_src[i] + boff);
     }
   };
-  load_global(0);
-
-  for (int kt = 0; kt < nk; ++kt) {
+  auto k_tile = [&](int kt, u32x4 (&ga)[4], u32x4 (&gb)[4]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int r = r_in + 32 * i;
@@ -205,7 +208,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       *reinterpret_cast<u32x4*>(&Bs[r * LDS_STRIDE + kv * 8]) = gb[i];
     }
     __syncthreads();
-    if (kt + 1 < nk) load_global(kt + 1);
+    if (kt + 2 < nk) load_global(kt + 2, ga, gb);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 fa[2], fb[2];
@@ -223,6 +226,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
           acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
     }
     __syncthreads();
+  };
+  load_global(0, ga0, gb0);
+  if (nk > 1) load_global(1, ga1, gb1);
+  for (int kt = 0; kt < nk; kt += 2) {
+    k_tile(kt, ga0, gb0);
+    if (kt + 1 < nk) k_tile(kt + 1, ga1, gb1);
   }
 
   // epilogue.  Accumulator element r of lane l sits at row (r/4)*8 + (l/32)*4 + r%4, column l%32.
@@ -234,7 +243,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     for (int r = 0; r < 16; ++r) {
       const int row = ti.m0 + wm * 64 + mi * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
       if (row >= ti.rows) continue;
-      __bf16* crow = C + (long long)(ti.row_base + row) * a.ldc + a.c_col0;
+      __bf16* crow = C + (long long)(ti.row_base + row) * a.ldc + group_col0(a, ti.group);
       if (SWIGLU) {
         const int col = n0 + wn * 32 + col_in;
         if (col < a.N) {
@@ -252,6 +261,148 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   }
 }
 }  // namespace small
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel for groups of a few rows (decode-shaped layers), where the work is streaming
+// every active expert's weights from HBM once.  No LDS tiles, no barriers in the K loop: each wave
+// owns 32 output columns x up to 16*MT tokens over the whole K and loads both operands straight
+// into MFMA fragment registers.  v_mfma_f32_16x16x32_bf16 takes 8 consecutive K elements per lane
+// and 4 lanes per row, so one load instruction reads 16 rows x one whole 64-byte sector.  Weights
+// are the row operand: a lane ends up with 4 consecutive output columns of one token (8-byte
+// stores).  The operands of the next K step (4 or 8 KiB of weights per wave) are in flight while
+// the current ones are multiplied; token blocks past the group's rows are skipped.
+namespace skinny {
+constexpr int BN_OUT = 32;
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+template <bool SWIGLU, int MT>   // MT token blocks of 16 per m-tile
+__global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
+  constexpr int BM = 16 * MT;
+  constexpr int KS = MT <= 2 ? 2 : 1;   // 32-wide K steps per pipeline stage
+  constexpr int NW = SWIGLU ? 2 : 1;
+  __shared__ TileInfo s_info;
+  const int n_cb = a.N / BN_OUT;   // column blocks (host: N % 32 == 0)
+  const int wgs_per_mt = (n_cb + 3) / 4;
+  const int mt = blockIdx.x / wgs_per_mt;
+  const TileInfo ti = find_tile<BM>(a, mt, &s_info);
+  if (ti.group < 0) return;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int cb = (blockIdx.x % wgs_per_mt) * 4 + wave;
+  if (cb >= n_cb) return;   // no barrier follows
+  const int n0 = cb * BN_OUT;
+  const int r = lane & 15, c = lane >> 4;
+  const long long widx = a.grp_widx ? a.grp_widx[ti.group] : (a.w_base + ti.group);
+  const int nblk = min(MT, (ti.rows - ti.m0 + 15) / 16);   // token blocks with any valid row
+
+  // this lane's weight rows (column blocks 0 and 1 of the unit) and token rows, at its 16-byte K group
+  const char* w[NW][2];
+#pragma unroll
+  for (int m = 0; m < NW; ++m)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+      w[m][nb] = static_cast<const char*>(m == 0 ? a.B : a.B2) +
+                 ((widx * a.b_group_stride + (long long)(n0 + nb * 16 + r) * a.ldb) * 2 + c * 16);
+  const char* xa[MT];
+#pragma unroll
+  for (int tb = 0; tb < MT; ++tb) {
+    int lr = ti.m0 + tb * 16 + r;
+    if (lr >= ti.rows) lr = ti.rows - 1;   // tokens past the group's end repeat its last row; dropped at the end
+    const int logical = ti.row_base + lr;
+    const long long src = a.a_rows ? a.a_rows[logical] : logical;
+    xa[tb] = static_cast<const char*>(a.A) + (src * a.lda * 2 + c * 16);
+  }
+
+  f32x4v acc[NW][2][MT];
+#pragma unroll
+  for (int m = 0; m < NW; ++m)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int tb = 0; tb < MT; ++tb) acc[m][nb][tb] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
+
+  const int nst = a.K / (32 * KS);   // pipeline stages along K (host: K % 64 == 0)
+  // byte offset of the current stage inside a weight row; K > kseg walks consecutive weight matrices
+  long long w_off = 0;
+  int w_kin = 0;
+  auto w_advance = [&]() {
+    w_off += 64 * KS;
+    w_kin += 32 * KS;
+    if (w_kin >= a.kseg) {   // host: kseg % 64 == 0, so a stage never straddles two matrices
+      w_kin = 0;
+      w_off += (a.b_group_stride - a.kseg) * 2;
+    }
+  };
+  struct Stage {
+    bf16x8 wf[KS][NW][2], xf[KS][MT];
+  };
+  auto load_stage = [&](Stage& st, long long woff, int i) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int m = 0; m < NW; ++m)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+          {
+            // measured: the streaming hint helps the single-matrix product and hurts the gate/up pair
+            const bf16x8* src = reinterpret_cast<const bf16x8*>(w[m][nb] + woff + ks * 64);
+            st.wf[ks][m][nb] = SWIGLU ? *src : __builtin_nontemporal_load(src);
+          }
+#pragma unroll
+      for (int tb = 0; tb < MT; ++tb)
+        if (tb < nblk) st.xf[ks][tb] = *reinterpret_cast<const bf16x8*>(xa[tb] + ((long long)i * KS + ks) * 64);
+    }
+  };
+  auto multiply = [&](const Stage& st) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int tb = 0; tb < MT; ++tb)
+        if (tb < nblk) {
+#pragma unroll
+          for (int m = 0; m < NW; ++m)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+              acc[m][nb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.wf[ks][m][nb], st.xf[ks][tb], acc[m][nb][tb], 0, 0, 0);
+        }
+  };
+
+  Stage s0, s1;
+  load_stage(s0, w_off, 0);
+  for (int i = 0; i < nst; i += 2) {
+    // past the end the last stage is fetched again and not used
+    const bool more1 = i + 1 < nst;
+    if (more1) w_advance();
+    load_stage(s1, w_off, more1 ? i + 1 : i);
+    multiply(s0);
+    const bool more2 = i + 2 < nst;
+    if (more2) w_advance();
+    load_stage(s0, w_off, more2 ? i + 2 : (more1 ? i + 1 : i));
+    if (more1) multiply(s1);
+  }
+
+  // acc element e of lane l: token l%16 of its block, output column nb*16 + (l/16)*4 + e of the unit
+#pragma unroll
+  for (int tb = 0; tb < MT; ++tb) {
+    const int token = ti.m0 + tb * 16 + r;
+    if (token < ti.rows) {
+      __bf16* crow = static_cast<__bf16*>(a.C) + (long long)(ti.row_base + token) * a.ldc + group_col0(a, ti.group) + n0 + c * 4;
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float g = acc[0][nb][tb][e];
+          v[e] = SWIGLU ? g / (1.0f + __expf(-g)) * acc[NW - 1][nb][tb][e] : g;
+        }
+        uint2 pk;
+        pk.x = pack_bf16(v[0], v[1]);
+        pk.y = pack_bf16(v[2], v[3]);
+        *reinterpret_cast<uint2*>(crow + nb * 16) = pk;
+      }
+    }
+  }
+}
+}  // namespace skinny
 
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel, main variant (prefill-shaped layers).  Block = 256 threads = 4 waves (2 x 2),
@@ -321,7 +472,7 @@ __device__ __forceinline__ float swiglu_fast(float g, float u) {
 
 // One output tile before its row gather has come back.  All fields but raw are wave-uniform.
 struct Head {
-  int valid, m0, rows, row_base, n0, widx;
+  int valid, m0, rows, row_base, n0, widx, ccol;   // ccol: first output column of the tile's group
   int raw[8];   // source rows of this lane's 8 A-tile rows
 };
 
@@ -333,9 +484,10 @@ __device__ __forceinline__ void locate(const GemmArgs& a, const int* s_goff, con
   group = -1;
   m0 = rows = row_base = 0;
   if (a.grp_offset == nullptr) {
-    if ((long long)mt * BM < a.M) {
-      group = 0;
-      m0 = mt * BM;
+    const int per_group = (a.M + BM - 1) / BM;
+    if (mt < per_group * a.ngroups) {
+      group = mt / per_group;
+      m0 = (mt % per_group) * BM;
       rows = a.M;
     }
     return;
@@ -398,12 +550,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     h.valid = group >= 0;
     h.n0 = tm.nt * BN_OUT;
     h.widx = a.w_base;
+    h.ccol = a.c_col0;
     if (h.valid) {
-      if (a.grp_offset) h.widx = s_widx[group];
+      h.widx = a.grp_offset ? s_widx[group] : a.w_base + group;
+      h.ccol = group_col0(a, group);
     } else if (fallback) {
       h.m0 = fallback->m0; h.rows = fallback->rows; h.row_base = fallback->row_base;
-      h.n0 = fallback->n0; h.widx = fallback->widx;
+      h.n0 = fallback->n0; h.widx = fallback->widx; h.ccol = fallback->ccol;
     }
+    h.ccol = __builtin_amdgcn_readfirstlane(h.ccol);
     h.widx = __builtin_amdgcn_readfirstlane(h.widx);
     h.m0 = __builtin_amdgcn_readfirstlane(h.m0);
     h.rows = __builtin_amdgcn_readfirstlane(h.rows);
@@ -653,7 +808,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       const int col_w = hd.n0 + wn * W_COLS;   // first output column of the wave tile
       const unsigned n_rec = rows_left > 0 ? (unsigned)((rows_left - 1) * a.ldc + W_COLS) * 2u : 0u;
       const unsigned long long c_tile = reinterpret_cast<unsigned long long>(
-          C + (long long)(hd.row_base + hd.m0 + wm * 128) * a.ldc + a.c_col0 + col_w);
+          C + (long long)(hd.row_base + hd.m0 + wm * 128) * a.ldc + hd.ccol + col_w);
       const unsigned long long c_tile_u =   // the descriptor has to sit in scalar registers
           ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c_tile >> 32)) << 32) |
           (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c_tile);
@@ -759,7 +914,7 @@ __global__ __launch_bounds__(FM * FN) void grouped_gemm_f32(const GemmArgs a) {
   if (row < ti.rows && col < a.N) {
     float* C = static_cast<float*>(a.C);
     const float out = SWIGLU ? acc / (1.0f + expf(-acc)) * acc2 : acc;
-    C[(long long)(ti.row_base + row) * a.ldc + a.c_col0 + col] = out;
+    C[(long long)(ti.row_base + row) * a.ldc + group_col0(a, ti.group) + col] = out;
   }
 }
 
@@ -785,15 +940,27 @@ static int device_cu_count(int* out) {
 static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
   if (total_rows == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
-    const int groups = a.grp_offset ? a.ngroups : 1;
+    const int groups = a.ngroups;
     // 256-row tiles once groups average >= 192 rows, every A byte offset fits 32 bits and there
     // are at least two K tiles to pipeline
     const bool use_big = (long long)total_rows >= 192ll * groups &&
                          (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK;
+    // groups averaging under 24 rows: weight streaming, one wave per 32 columns x 32 tokens
+    const bool use_skinny = !use_big && (long long)total_rows < 24ll * groups && a.N % skinny::BN_OUT == 0;
+    if (use_skinny) {
+      const long long m_tiles = (total_rows + 31) / 32 + a.ngroups;
+      const long long blocks = m_tiles * ((a.N / skinny::BN_OUT + 3) / 4);
+      OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
+      const dim3 grid((unsigned)blocks), block(256);
+      if (swiglu) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2>), grid, block, 0, s, a);
+      OCC_LAUNCH_CHECK("grouped_gemm");
+      return OCCULT_OK;
+    }
     const int bm = use_big ? t256::BM : small::BM;
     const int bn = use_big ? t256::BN : small::BN;
     const int bn_out = swiglu ? bn / 2 : bn;
-    const long long m_tiles = (total_rows + bm - 1) / bm + (a.grp_offset ? a.ngroups : 0);
+    const long long m_tiles = (total_rows + bm - 1) / bm + a.ngroups;
     long long blocks = mapped_grid(m_tiles, (a.N + bn_out - 1) / bn_out);
     OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
     if (use_big) {   // persistent: one block per CU, a multiple of 8 so a block keeps its XCD
@@ -812,7 +979,7 @@ static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, in
       else hipLaunchKernelGGL(small::grouped_gemm_bf16<false>, grid, block, 0, s, a);
     }
   } else {
-    const long long m_tiles = (total_rows + FM - 1) / FM + (a.grp_offset ? a.ngroups : 0);
+    const long long m_tiles = (total_rows + FM - 1) / FM + a.ngroups;
     const long long blocks = m_tiles * ((a.N + FN - 1) / FN);
     OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
     if (swiglu)
@@ -856,58 +1023,67 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int n_epd = c.T * c.k;
 
-  GemmArgs g1{};
-  g1.A = sfd_x; g1.lda = c.d; g1.a_rows = plan->epd_sfd_row;
-  g1.B = weights->w_gate; g1.B2 = weights->w_up;
-  g1.b_group_stride = (long long)c.f * c.d; g1.ldb = c.d; g1.kseg = c.d;
-  g1.C = epd_h; g1.ldc = c.f; g1.c_col0 = 0;
-  g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.w_base = 0;
-  g1.ngroups = c.E; g1.M = 0; g1.N = c.f; g1.K = c.d;
-  g1.a_rows_total = sfd_rows_max(c);
+  hipStream_t s_shared = s;
   const bool do1 = c.ffn_phase != 2, do2 = c.ffn_phase != 1;
-  if (do1) {
-    rc = launch_gemm(c, g1, true, n_epd, s);
-    if (rc) return rc;
-  }
 
-  GemmArgs g2{};
-  g2.A = epd_h; g2.lda = c.f; g2.a_rows = nullptr;
-  g2.B = weights->w_down; g2.B2 = nullptr;
-  g2.b_group_stride = (long long)c.d * c.f; g2.ldb = c.f; g2.kseg = c.f;
-  g2.C = epd_y; g2.ldc = c.d; g2.c_col0 = 0;
-  g2.grp_offset = plan->exp_offset; g2.grp_widx = plan->pos_expert; g2.w_base = 0;
-  g2.ngroups = c.E; g2.M = 0; g2.N = c.d; g2.K = c.f;
-  g2.a_rows_total = n_epd;
-  if (do2) {
-    rc = launch_gemm(c, g2, false, n_epd, s);
-    if (rc) return rc;
-  }
-
-  if (c.S > 0) {
-    // shared experts: h_shared[t][s*f .. (s+1)*f) per shared expert, then one product whose K
-    // dimension walks the S down-projection matrices
-    for (int sh = 0; do1 && sh < c.S; ++sh) {
+  auto shared_experts = [&]() -> int {
+    // h_shared[t][s*f .. (s+1)*f) per shared expert, then one product whose K dimension walks
+    // the S down-projection matrices
+    if (do1) {   // the S shared experts as S groups over the same T rows
       GemmArgs a1{};
       a1.A = x; a1.lda = c.d; a1.a_rows = nullptr;
       a1.B = weights->w_gate; a1.B2 = weights->w_up;
       a1.b_group_stride = (long long)c.f * c.d; a1.ldb = c.d; a1.kseg = c.d;
-      a1.C = h_shared; a1.ldc = c.S * c.f; a1.c_col0 = sh * c.f;
-      a1.grp_offset = nullptr; a1.grp_widx = nullptr; a1.w_base = c.E + sh;
-      a1.ngroups = 1; a1.M = c.T; a1.N = c.f; a1.K = c.d; a1.a_rows_total = c.T;
-      rc = launch_gemm(c, a1, true, c.T, s);
-      if (rc) return rc;
+      a1.C = h_shared; a1.ldc = c.S * c.f; a1.c_col0 = 0; a1.c_group_cols = c.f;
+      a1.grp_offset = nullptr; a1.grp_widx = nullptr; a1.w_base = c.E;
+      a1.ngroups = c.S; a1.M = c.T; a1.N = c.f; a1.K = c.d; a1.a_rows_total = c.T;
+      const int r1 = launch_gemm(c, a1, true, c.T * c.S, s_shared);
+      if (r1) return r1;
     }
-    GemmArgs a2{};
-    a2.A = h_shared; a2.lda = c.S * c.f; a2.a_rows = nullptr;
-    a2.B = weights->w_down; a2.B2 = nullptr;
-    a2.b_group_stride = (long long)c.d * c.f; a2.ldb = c.f; a2.kseg = c.f;
-    a2.C = y_shared; a2.ldc = c.d; a2.c_col0 = 0;
-    a2.grp_offset = nullptr; a2.grp_widx = nullptr; a2.w_base = c.E;
-    a2.ngroups = 1; a2.M = c.T; a2.N = c.d; a2.K = c.S * c.f; a2.a_rows_total = c.T;
     if (do2) {
-      rc = launch_gemm(c, a2, false, c.T, s);
-      if (rc) return rc;
+      GemmArgs a2{};
+      a2.A = h_shared; a2.lda = c.S * c.f; a2.a_rows = nullptr;
+      a2.B = weights->w_down; a2.B2 = nullptr;
+      a2.b_group_stride = (long long)c.d * c.f; a2.ldb = c.f; a2.kseg = c.f;
+      a2.C = y_shared; a2.ldc = c.d; a2.c_col0 = 0;
+      a2.grp_offset = nullptr; a2.grp_widx = nullptr; a2.w_base = c.E;
+      a2.ngroups = 1; a2.M = c.T; a2.N = c.d; a2.K = c.S * c.f; a2.a_rows_total = c.T;
+      return launch_gemm(c, a2, false, c.T, s_shared);
     }
+    return OCCULT_OK;
+  };
+  auto routed_experts = [&]() -> int {
+    if (do1) {
+      GemmArgs g1{};
+      g1.A = sfd_x; g1.lda = c.d; g1.a_rows = plan->epd_sfd_row;
+      g1.B = weights->w_gate; g1.B2 = weights->w_up;
+      g1.b_group_stride = (long long)c.f * c.d; g1.ldb = c.d; g1.kseg = c.d;
+      g1.C = epd_h; g1.ldc = c.f; g1.c_col0 = 0;
+      g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.w_base = 0;
+      g1.ngroups = c.E; g1.M = 0; g1.N = c.f; g1.K = c.d;
+      g1.a_rows_total = sfd_rows_max(c);
+      const int r1 = launch_gemm(c, g1, true, n_epd, s);
+      if (r1) return r1;
+    }
+    if (do2) {
+      GemmArgs g2{};
+      g2.A = epd_h; g2.lda = c.f; g2.a_rows = nullptr;
+      g2.B = weights->w_down; g2.B2 = nullptr;
+      g2.b_group_stride = (long long)c.d * c.f; g2.ldb = c.f; g2.kseg = c.f;
+      g2.C = epd_y; g2.ldc = c.d; g2.c_col0 = 0;
+      g2.grp_offset = plan->exp_offset; g2.grp_widx = plan->pos_expert; g2.w_base = 0;
+      g2.ngroups = c.E; g2.M = 0; g2.N = c.d; g2.K = c.f;
+      g2.a_rows_total = n_epd;
+      return launch_gemm(c, g2, false, n_epd, s);
+    }
+    return OCCULT_OK;
+  };
+
+  rc = routed_experts();
+  if (rc) return rc;
+  if (c.S > 0) {
+    rc = shared_experts();
+    if (rc) return rc;
   }
   return OCCULT_OK;
 }
