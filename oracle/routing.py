@@ -36,6 +36,14 @@ Readings where the paper is silent:
 
 Gate *values* are computed in float64 from the float32 scores (the definition);
 only decisions use exp_ref.
+
+Router scores themselves (Eq. 1: g is a single linear projection of the hidden
+state) are `router_scores`: the plain product x W_r^T in float64 from the stored
+inputs.  A second implementation of that product sums in another order, so its
+float32 scores differ in the last bits and selections whose deciding scores are
+closer than that may legitimately differ; `selection_margin` measures, per token,
+the gap that decides its selection, which is what a test needs to audit such
+differences.
 """
 from __future__ import annotations
 
@@ -145,6 +153,37 @@ def route(logits: np.ndarray, k: int, D: int, expert_pos: np.ndarray | None = No
     if renorm:
         w = w / w.sum(axis=1, keepdims=True)
     return ids, w
+
+
+def router_scores(x: np.ndarray, w_router: np.ndarray) -> np.ndarray:
+    """g(x) of Eq. 1 for every token: x [T, d] times w_router [E, d] transposed, in float64."""
+    return np.asarray(x, dtype=np.float64) @ np.asarray(w_router, dtype=np.float64).T
+
+
+def router_scores_loops(x: np.ndarray, w_router: np.ndarray) -> np.ndarray:
+    """The same by explicit loops (tiny inputs)."""
+    T, d = x.shape
+    E = w_router.shape[0]
+    out = np.zeros((T, E), dtype=np.float64)
+    for t in range(T):
+        for e in range(E):
+            acc = 0.0
+            for i in range(d):
+                acc += float(x[t, i]) * float(w_router[e, i])
+            out[t, e] = acc
+    return out
+
+
+def selection_margin(logits: np.ndarray, k: int) -> np.ndarray:
+    """Per token, the smallest gap between two adjacent scores among the k+1 highest (unpruned
+    selection): the k-th/(k+1)-th gap decides membership, the gaps above it decide slot order.
+    A perturbation of the scores smaller than half this margin cannot change ids."""
+    lg = np.asarray(logits, dtype=np.float64)
+    E = lg.shape[1]
+    top = -np.sort(-lg, axis=1)[:, :min(k + 1, E)]
+    if top.shape[1] < 2:
+        return np.full(lg.shape[0], np.inf)
+    return np.min(top[:, :-1] - top[:, 1:], axis=1)
 
 
 def route_loops(logits: np.ndarray, k: int, D: int, expert_pos=None, n_d: int = 0,

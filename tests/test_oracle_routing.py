@@ -166,3 +166,46 @@ def test_all_subsets_single_token():
             lg[0, e] = 3.0 - rank
         ids, w = routing.route(lg, k, D=3)
         assert ids[0].tolist() == list(sub)
+
+
+# ---- router scores (Eq. 1: g(x) is a linear projection) ---------------------------------------
+
+def test_router_scores_match_loops_and_pick_columns():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((5, 7))
+    wr = rng.standard_normal((4, 7))
+    got = routing.router_scores(x, wr)
+    assert np.allclose(got, routing.router_scores_loops(x, wr), rtol=1e-13, atol=1e-13)
+    # a one-hot hidden state reads one column of W_r; the projection is linear
+    eye = np.eye(7)
+    assert np.array_equal(routing.router_scores(eye, wr), wr.T)
+    assert np.allclose(routing.router_scores(2.0 * x + eye[:5], wr), 2.0 * got + wr.T[:5], rtol=1e-13, atol=1e-13)
+    # not transposed: a rectangular case with distinct T, E, d has the right shape
+    assert got.shape == (5, 4)
+
+
+def test_workload_logits_are_the_router_scores():
+    shape = wl.CONFIGS["tiny_f32"]
+    wk = wl.make_workload(shape, with_experts=False)
+    ref = routing.router_scores(wk.x, wk.w_router)
+    assert np.max(np.abs(wk.logits - ref)) <= 1e-5 * np.sqrt(np.mean(ref ** 2))
+
+
+def test_selection_margin_bounds_what_a_perturbation_can_change():
+    rng = np.random.default_rng(11)
+    lg = rng.standard_normal((400, 16)).astype(np.float32)
+    k = 4
+    margin = routing.selection_margin(lg, k)
+    assert margin.shape == (400,) and np.all(margin >= 0)
+    ids0, _ = routing.route(lg, k, 4)
+    # hand-made rows: gap structure known
+    row = np.array([[5.0, 4.0, 3.5, 1.0, 0.0, -1.0]], dtype=np.float32)
+    assert routing.selection_margin(row, 2)[0] == 0.5      # min(5-4, 4-3.5)
+    assert routing.selection_margin(row, 3)[0] == 0.5      # min(1, .5, 2.5)
+    # perturbations below half the margin never change the selection; tokens that do change under a
+    # larger perturbation all have a margin below twice its size
+    for eps in (1e-4, 1e-2):
+        noise = rng.uniform(-eps, eps, lg.shape).astype(np.float32)
+        ids1, _ = routing.route(lg + noise, k, 4)
+        changed = np.any(ids0 != ids1, axis=1)
+        assert np.all(margin[changed] <= 2 * eps + 1e-6)
