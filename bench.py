@@ -112,6 +112,8 @@ def main():
     x = torch.from_numpy(wk.x).to(dev).to(tdt)
     wg, wu, wd = (torch.from_numpy(a).to(dev).to(tdt) for a in (wk.w_gate, wk.w_up, wk.w_down))
     C = torch.zeros((shape.E, shape.E), dtype=torch.int32, device=dev)
+    w_router = torch.from_numpy(wk.w_router).to(dev).to(tdt)
+    logits_gpu = torch.empty_like(logits)
 
     def step():
         layer.route(logits)
@@ -148,7 +150,11 @@ def main():
         "expert_ffn": _event_time_ms(lambda: layer.expert_ffn(x, wg, wu, wd), r),
         "combine": _event_time_ms(lambda: layer.combine(), r),
         "coactivation": _event_time_ms(lambda: B.occult_coactivation(layer.cfg, layer.ids, C, False), r),
+        # not part of the step (which starts from the workload's scores): projection x W_r^T fused with routing
+        "router_projection_and_route": _event_time_ms(lambda: layer.route_from_hidden(x, w_router, logits_gpu), r),
     }
+    layer.route(logits)      # the step's own routing back in place for the phase timings below
+    layer.make_plan()
     layer.cfg.ffn_phase = 1
     calls["ffn_gemm1_swiglu"] = _event_time_ms(lambda: layer.expert_ffn(x, wg, wu, wd), r)
     layer.cfg.ffn_phase = 2
@@ -165,7 +171,10 @@ def main():
     bytes_combine = (n_epd + n_sfd + T + (T if S else 0)) * row   # fused two-stage combine
     tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12
     gbs = lambda by, ms: by / (ms * 1e-3) / 1e9
+    bytes_router = (T * d + shape.E * d) * es + T * shape.E * 4 + T * k * 8
     rooflines = {
+        "router_projection_and_route": {"bound": "hbm", "achieved": gbs(bytes_router, calls["router_projection_and_route"]),
+                                        "peak": PEAK_HBM_GBS, "unit": "GB/s"},
         "ffn_gemm1_swiglu": {"bound": "mfma", "achieved": tf(flops1, calls["ffn_gemm1_swiglu"]),
                              "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"},
         "ffn_gemm2_down": {"bound": "mfma", "achieved": tf(flops2, calls["ffn_gemm2_down"]),

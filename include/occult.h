@@ -140,6 +140,15 @@ int occult_plan_bind(const occult_cfg_t* cfg, void* plan_mem, size_t plan_bytes,
 int occult_route(const occult_cfg_t* cfg, const float* logits, int32_t* ids, float* w,
                  occult_stream_t stream);
 
+/* Router projection + routing in one call (paper Eq. 1: g(x) is a single linear projection of the
+ * hidden state, followed by Softmax and top-k as in occult_route).  x [T][d] and w_router [E][d]
+ * in cfg.dtype (device ptrs, 16-byte aligned; bf16 needs d % 128 == 0); writes the scores
+ * logits [T][E] f32 = x w_router^T (f32 accumulation; the summation order is fixed, so the scores
+ * are reproducible run to run, but they differ in the last bits from a product summed in
+ * another order) and routes them exactly as occult_route would: ids [T][k], w [T][k]. */
+int occult_router(const occult_cfg_t* cfg, const void* x, const void* w_router, float* logits,
+                  int32_t* ids, float* w, occult_stream_t stream);
+
 /* Planner (paper App. A.2 "Building BRIM_0" / "Building BRIM_1" for all D simulated devices at
  * once; Sec. 2.2 replica count).  ids [T][k] i32, w [T][k] f32 device ptrs; fills every table of
  * `plan`.  `ws` device ptr of >= workspace_bytes.  Bit-reproducible (no atomics). */

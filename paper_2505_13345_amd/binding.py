@@ -21,7 +21,7 @@ OCCULT_F32, OCCULT_BF16 = 0, 1
 EXPORTS = [
     "occult_version", "occult_last_error", "occult_plan_sizes", "occult_plan_bind", "occult_route",
     "occult_plan", "occult_dispatch", "occult_expert_ffn", "occult_combine", "occult_coactivation",
-    "occult_placement_greedy", "occult_plan_stats",
+    "occult_placement_greedy", "occult_plan_stats", "occult_router",
 ]
 
 
@@ -76,6 +76,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_plan_sizes.argtypes = [cfgp, POINTER(c_size_t), POINTER(c_size_t)]
     lib.occult_plan_bind.argtypes = [cfgp, c_void_p, c_size_t, planp]
     lib.occult_route.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.occult_router.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_plan.argtypes = [cfgp, c_void_p, c_void_p, planp, c_void_p, c_size_t, c_void_p]
     lib.occult_dispatch.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p]
     lib.occult_expert_ffn.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t),
@@ -138,6 +139,11 @@ def occult_plan_bind(cfg: occult_cfg_t, plan_mem) -> occult_plan_t:
 
 def occult_route(cfg, logits, ids, w, stream=None) -> None:
     _check(load_library().occult_route(ctypes.byref(cfg), _ptr(logits), _ptr(ids), _ptr(w), _stream(stream)))
+
+
+def occult_router(cfg, x, w_router, logits, ids, w, stream=None) -> None:
+    _check(load_library().occult_router(ctypes.byref(cfg), _ptr(x), _ptr(w_router), _ptr(logits), _ptr(ids), _ptr(w),
+                                        _stream(stream)))
 
 
 def occult_plan(cfg, ids, w, plan: occult_plan_t, ws, stream=None) -> None:

@@ -61,27 +61,18 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 constexpr int kRouteWavesPerBlock = 4;
 
+// Routes one token on one wavefront.  `row` points at the token's E scores (global or LDS);
+// s_dev[e] is the device of expert e.  Lane s < k writes slot s.
 template <int EPL>  // experts per lane = ceil(E / 64)
-__global__ __launch_bounds__(kRouteWavesPerBlock * 64) void route_kernel(
-    const float* __restrict__ logits, int T, int E, int k, int D, int G,
-    const int32_t* __restrict__ expert_pos, int n_d, int prune_mode, int renorm,
-    int32_t* __restrict__ ids, float* __restrict__ w) {
-  __shared__ int s_dev[OCCULT_MAX_E];
-  for (int e = threadIdx.x; e < E; e += blockDim.x)
-    s_dev[e] = (expert_pos ? expert_pos[e] : e) / G;
-  __syncthreads();
-
-  const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * kRouteWavesPerBlock + (threadIdx.x >> 6);
-  if (t >= T) return;   // whole wave leaves together; no barrier follows
-
+__device__ __forceinline__ void route_one(const float* row, int lane, int E, int k, int D, const int* s_dev,
+                                          int n_d, int prune_mode, int renorm, int32_t* ids_t, float* w_t) {
   const float kNegInf = -INFINITY;
   float v0[EPL];   // the token's scores as read (with -0.0 folded onto +0.0)
   float v[EPL];    // working copy: taken / disallowed entries become -inf
 #pragma unroll
   for (int i = 0; i < EPL; ++i) {
     const int e = lane + 64 * i;
-    v0[i] = (e < E) ? (logits[(size_t)t * E + e] + 0.0f) : kNegInf;
+    v0[i] = (e < E) ? (row[e] + 0.0f) : kNegInf;
     v[i] = v0[i];
   }
 
@@ -173,9 +164,145 @@ __global__ __launch_bounds__(kRouteWavesPerBlock * 64) void route_kernel(
     g = g / sel;
   }
   if (lane < k) {
-    ids[(size_t)t * k + lane] = my_id;
-    w[(size_t)t * k + lane] = g;
+    ids_t[lane] = my_id;
+    w_t[lane] = g;
   }
+}
+
+template <int EPL>
+__global__ __launch_bounds__(kRouteWavesPerBlock * 64) void route_kernel(
+    const float* __restrict__ logits, int T, int E, int k, int D, int G,
+    const int32_t* __restrict__ expert_pos, int n_d, int prune_mode, int renorm,
+    int32_t* __restrict__ ids, float* __restrict__ w) {
+  __shared__ int s_dev[OCCULT_MAX_E];
+  for (int e = threadIdx.x; e < E; e += blockDim.x)
+    s_dev[e] = (expert_pos ? expert_pos[e] : e) / G;
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * kRouteWavesPerBlock + (threadIdx.x >> 6);
+  if (t >= T) return;   // whole wave leaves together; no barrier follows
+  route_one<EPL>(logits + (size_t)t * E, lane, E, k, D, s_dev, n_d, prune_mode, renorm, ids + (size_t)t * k,
+                 w + (size_t)t * k);
+}
+
+// ------------------------------------------------------------------------------------------
+// Router projection g(x) = x W_r^T (paper Eq. 1) fused with the routing above, bf16 inputs.
+// The work is reading x once: a block takes 32 tokens, its 4 waves take a quarter of the hidden
+// dimension each and multiply it with all E expert rows on v_mfma_f32_16x16x32_bf16 (operands
+// loaded straight into fragment registers: 16 rows x one 64-byte sector per load; the expert
+// rows come from cache).  The four partial products are added in LDS in wave order (a fixed
+// order, so scores are reproducible), written out as float32, and each wave then routes 8 of the
+// block's tokens from LDS.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+constexpr int kRouterTokens = 32;
+
+template <int EB>   // blocks of 16 experts, E <= 16 * EB
+__global__ __launch_bounds__(256) void router_kernel(const __bf16* __restrict__ x, const __bf16* __restrict__ wr,
+                                                     int T, int d, int E, int k, int D, int G,
+                                                     const int32_t* __restrict__ expert_pos, int n_d,
+                                                     int prune_mode, int renorm, float* __restrict__ logits,
+                                                     int32_t* __restrict__ ids, float* __restrict__ w) {
+  constexpr int EPL = EB <= 4 ? 1 : EB / 4;
+  constexpr int LSTRIDE = 16 * EB + 4;
+  __shared__ __attribute__((aligned(16))) float s_lg[kRouterTokens * LSTRIDE];
+  __shared__ int s_dev[OCCULT_MAX_E];
+  for (int e = threadIdx.x; e < E; e += blockDim.x)
+    s_dev[e] = (expert_pos ? expert_pos[e] : e) / G;
+
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane & 15, c = lane >> 4;
+  const int tok0 = blockIdx.x * kRouterTokens;
+  const int kq = d / 4;   // host: d % 128 == 0
+  const size_t koff = ((size_t)wave * kq + c * 8) * 2;
+  const char* xp[2];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb) {
+    const int t = min(tok0 + tb * 16 + r, T - 1);   // rows past the end repeat the last token; not written
+    xp[tb] = reinterpret_cast<const char*>(x) + (size_t)t * d * 2 + koff;
+  }
+  const char* wp[EB];
+#pragma unroll
+  for (int eb = 0; eb < EB; ++eb) {
+    const int e = min(eb * 16 + r, E - 1);
+    wp[eb] = reinterpret_cast<const char*>(wr) + (size_t)e * d * 2 + koff;
+  }
+  f32x4v acc[2][EB];
+#pragma unroll
+  for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb) acc[tb][eb] = f32x4v{0.0f, 0.0f, 0.0f, 0.0f};
+
+  struct Stage {
+    bf16x8 xf[2], wf[EB];
+  };
+  auto load_stage = [&](Stage& st, int i) {
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) st.xf[tb] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(xp[tb] + (size_t)i * 64));
+#pragma unroll
+    for (int eb = 0; eb < EB; ++eb) st.wf[eb] = *reinterpret_cast<const bf16x8*>(wp[eb] + (size_t)i * 64);
+  };
+  auto multiply = [&](const Stage& st) {
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int eb = 0; eb < EB; ++eb)
+        acc[tb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.wf[eb], st.xf[tb], acc[tb][eb], 0, 0, 0);
+  };
+  const int nst = kq / 32;
+  Stage s0, s1;
+  load_stage(s0, 0);
+  for (int i = 0; i < nst; i += 2) {
+    const bool more1 = i + 1 < nst;
+    load_stage(s1, more1 ? i + 1 : i);   // past the end the last step is fetched again and not used
+    multiply(s0);
+    load_stage(s0, i + 2 < nst ? i + 2 : i);
+    if (more1) multiply(s1);
+  }
+
+  // acc[tb][eb] element j of lane l: token tb*16 + l%16, expert eb*16 + (l/16)*4 + j
+#pragma unroll
+  for (int turn = 0; turn < 4; ++turn) {
+    if (wave == turn) {
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb) {
+          f32x4v* dst = reinterpret_cast<f32x4v*>(&s_lg[(tb * 16 + r) * LSTRIDE + eb * 16 + c * 4]);
+          f32x4v v = acc[tb][eb];
+          if (turn > 0) {
+            const f32x4v old = *dst;
+            v = old + v;
+          }
+          *dst = v;
+        }
+    }
+    __syncthreads();
+  }
+
+  for (int j = 0; j < kRouterTokens / 4; ++j) {
+    const int tl = wave * (kRouterTokens / 4) + j;
+    const int t = tok0 + tl;
+    if (t >= T) break;   // wave-uniform; no barrier follows
+    const float* row = &s_lg[tl * LSTRIDE];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+      if (lane + 64 * i < E) logits[(size_t)t * E + lane + 64 * i] = row[lane + 64 * i];
+    route_one<EPL>(row, lane, E, k, D, s_dev, n_d, prune_mode, renorm, ids + (size_t)t * k, w + (size_t)t * k);
+  }
+}
+
+// float32 inputs (parity configuration): one thread per (token, expert), K summed in order
+__global__ __launch_bounds__(256) void router_f32_kernel(const float* __restrict__ x, const float* __restrict__ wr,
+                                                         int T, int d, int E, float* __restrict__ logits) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)T * E) return;
+  const float* xr = x + (i / E) * d;
+  const float* wrow = wr + (i % E) * d;
+  float acc = 0.0f;
+  for (int q = 0; q < d; ++q) acc = acc + xr[q] * wrow[q];
+  logits[i] = acc;
 }
 
 }  // namespace occult
@@ -204,5 +331,39 @@ extern "C" int occult_route(const occult_cfg_t* cfg, const float* logits, int32_
   }
 #undef OCC_ROUTE_LAUNCH
   OCC_LAUNCH_CHECK("route_kernel");
+  return OCCULT_OK;
+}
+
+extern "C" int occult_router(const occult_cfg_t* cfg, const void* x, const void* w_router, float* logits,
+                             int32_t* ids, float* w, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  if (c.T == 0) return OCCULT_OK;
+  OCC_REQUIRE(x && w_router && logits && ids && w, OCCULT_ENULLPTR, "x, w_router, logits, ids or w is NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int G = c.E / c.D;
+  if (c.dtype == OCCULT_F32) {
+    const size_t n = (size_t)c.T * c.E;
+    hipLaunchKernelGGL(router_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       static_cast<const float*>(x), static_cast<const float*>(w_router), c.T, c.d, c.E, logits);
+    OCC_LAUNCH_CHECK("router_f32_kernel");
+    return occult_route(cfg, logits, ids, w, stream);
+  }
+  OCC_REQUIRE(c.d % 128 == 0, OCCULT_ESHAPE, "bf16 router needs d to be a multiple of 128 (d=%d)", c.d);
+  OCC_REQUIRE(aligned16(x) && aligned16(w_router), OCCULT_EALIGN, "x or w_router is not 16-byte aligned");
+  const dim3 grid((c.T + kRouterTokens - 1) / kRouterTokens), block(256);
+  const int eb = (c.E + 15) / 16;
+#define OCC_ROUTER_LAUNCH(N)                                                                              \
+  hipLaunchKernelGGL(router_kernel<N>, grid, block, 0, s, static_cast<const __bf16*>(x),                   \
+                     static_cast<const __bf16*>(w_router), c.T, c.d, c.E, c.k, c.D, G, c.expert_pos, c.n_d, \
+                     c.prune_mode, c.renorm, logits, ids, w)
+  if (eb <= 1) OCC_ROUTER_LAUNCH(1);
+  else if (eb <= 2) OCC_ROUTER_LAUNCH(2);
+  else if (eb <= 4) OCC_ROUTER_LAUNCH(4);
+  else if (eb <= 8) OCC_ROUTER_LAUNCH(8);
+  else OCC_ROUTER_LAUNCH(16);
+#undef OCC_ROUTER_LAUNCH
+  OCC_LAUNCH_CHECK("router_kernel");
   return OCCULT_OK;
 }

@@ -47,6 +47,10 @@ class OccultLayer:
     def route(self, logits):
         B.occult_route(self.cfg, logits, self.ids, self.w)
 
+    def route_from_hidden(self, x, w_router, logits_out):
+        """Router projection x w_router^T -> logits_out [T, E] f32, then routing, in one call."""
+        B.occult_router(self.cfg, x, w_router, logits_out, self.ids, self.w)
+
     def make_plan(self, ids=None, w=None):
         B.occult_plan(self.cfg, self.ids if ids is None else ids, self.w if w is None else w,
                       self.plan, self.ws)
