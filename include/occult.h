@@ -140,7 +140,7 @@ int occult_plan_bind(const occult_cfg_t* cfg, void* plan_mem, size_t plan_bytes,
 int occult_route(const occult_cfg_t* cfg, const float* logits, int32_t* ids, float* w,
                  occult_stream_t stream);
 
-/* Router projection + routing in one call (paper Eq. 1: g(x) is a single linear projection of the
+/* Router projection, then routing, in one call (paper Eq. 1: g(x) is a single linear projection of the
  * hidden state, followed by Softmax and top-k as in occult_route).  x [T][d] and w_router [E][d]
  * in cfg.dtype (device ptrs, 16-byte aligned; bf16 needs d % 128 == 0); writes the scores
  * logits [T][E] f32 = x w_router^T (f32 accumulation; the summation order is fixed, so the scores
