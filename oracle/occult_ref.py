@@ -199,6 +199,8 @@ class OccultTrace:
     x_sfd: np.ndarray | None      # dispatched hidden rows (the all-to-all payload)
     y_sfd: np.ndarray | None      # merged expert outputs per SFD row (the return payload)
     y: np.ndarray | None          # layer output, ORI order
+    ids_sfd: np.ndarray | None = None   # routing of each dispatched row's token (rides along with the payload)
+    w_sfd: np.ndarray | None = None
 
 
 def moe_forward(x, ids, w, expert_pos, D, w_gate=None, w_up=None, w_down=None, S=0,
@@ -267,7 +269,7 @@ def moe_forward(x, ids, w, expert_pos, D, w_gate=None, w_up=None, w_down=None, S
                 y += (silu(g) * u) @ w_down[E + s].astype(acc).T
     n_sfd = int(dev_count.sum())
     return OccultTrace(brim_0, dev_count, brim_1_all, brim_w_all, n_sfd, n_epd, n_sfd / T,
-                       x_sfd, y_sfd, y)
+                       x_sfd, y_sfd, y, ids_sfd, w_sfd)
 
 
 def exchange_bytes(T: int, k: int, n_sfd: int, row_bytes: int):

@@ -266,3 +266,31 @@ def test_config_workloads_replica_statistics():
     tr_p = occult_ref.moe_forward(np.zeros((shape.T, 1)), ids_p, w_p,
                                   wl.contiguous_placement(shape.E, shape.D), shape.D)
     assert tr_p.c_t <= 2.0 and tr_p.c_t > 1.9
+
+
+def test_dispatched_routing_metadata_rides_with_each_row():
+    """The first exchange carries ids and w of every dispatched row (App. A.2, pipeline listing):
+    each SFD row holds its token's routing, and was sent because that routing names an expert of
+    the receiving device."""
+    rng = np.random.default_rng(21)
+    T, E, D, k, d = 57, 12, 4, 3, 8
+    G = E // D
+    lg = rng.standard_normal((T, E)).astype(np.float32)
+    ids, w = routing.route(lg, k, D)
+    pos = wl.random_placement(E, D, seed=9)
+    x = rng.standard_normal((T, d))
+    tr = occult_ref.moe_forward(x, ids, w, pos, D)
+    offs = np.concatenate([[0], np.cumsum(tr.dev_count)])
+    seen = 0
+    for j in range(D):
+        for t in range(T):
+            r = tr.brim_0[j, t]
+            if r < 0:
+                assert not np.any(pos[ids[t]] // G == j)
+                continue
+            seen += 1
+            assert offs[j] <= r < offs[j + 1]
+            assert np.array_equal(tr.ids_sfd[r], ids[t]) and np.array_equal(tr.w_sfd[r], w[t])
+            assert np.array_equal(tr.x_sfd[r], x[t])
+            assert np.any(pos[tr.ids_sfd[r]] // G == j)
+    assert seen == tr.n_sfd == tr.ids_sfd.shape[0]
