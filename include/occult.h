@@ -160,6 +160,14 @@ int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
 int occult_dispatch(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* x, void* sfd_x,
                     occult_stream_t stream);
 
+/* Routing metadata of the dispatched rows (paper App. A.2, pipeline: ids and w travel with the
+ * hidden rows on the first exchange, and the receiving device builds BRIM_1 from them):
+ * sfd_ids[r][:] = ids[t][:] and sfd_w[r][:] = w[t][:] for every SFD row r of token t.
+ * ids [T][k] i32, w [T][k] f32, sfd_ids [>= N_sfd][k] i32, sfd_w [>= N_sfd][k] f32, device ptrs
+ * (allocate T*min(k,D) rows).  Rows beyond N_sfd are not written. */
+int occult_dispatch_meta(const occult_cfg_t* cfg, const occult_plan_t* plan, const int32_t* ids,
+                         const float* w, int32_t* sfd_ids, float* sfd_w, occult_stream_t stream);
+
 /* Expert computing (paper App. A.2 "SMM with Scattering" and the GEMM of "SMM with Merging"),
  * SwiGLU experts: for EPD row r of the expert at position P with SFD source row s = epd_sfd_row[r]:
  *   epd_h[r] = silu(W_gate sfd_x[s]) * (W_up sfd_x[s])      [N_epd][f]

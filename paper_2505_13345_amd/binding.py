@@ -21,7 +21,7 @@ OCCULT_F32, OCCULT_BF16 = 0, 1
 EXPORTS = [
     "occult_version", "occult_last_error", "occult_plan_sizes", "occult_plan_bind", "occult_route",
     "occult_plan", "occult_dispatch", "occult_expert_ffn", "occult_combine", "occult_coactivation",
-    "occult_placement_greedy", "occult_plan_stats", "occult_router",
+    "occult_placement_greedy", "occult_plan_stats", "occult_router", "occult_dispatch_meta",
 ]
 
 
@@ -79,6 +79,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_router.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_plan.argtypes = [cfgp, c_void_p, c_void_p, planp, c_void_p, c_size_t, c_void_p]
     lib.occult_dispatch.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p]
+    lib.occult_dispatch_meta.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_expert_ffn.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t),
                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_combine.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -154,6 +155,11 @@ def occult_plan(cfg, ids, w, plan: occult_plan_t, ws, stream=None) -> None:
 def occult_dispatch(cfg, plan, x, sfd_x, stream=None) -> None:
     _check(load_library().occult_dispatch(ctypes.byref(cfg), ctypes.byref(plan), _ptr(x), _ptr(sfd_x),
                                           _stream(stream)))
+
+
+def occult_dispatch_meta(cfg, plan, ids, w, sfd_ids, sfd_w, stream=None) -> None:
+    _check(load_library().occult_dispatch_meta(ctypes.byref(cfg), ctypes.byref(plan), _ptr(ids), _ptr(w),
+                                               _ptr(sfd_ids), _ptr(sfd_w), _stream(stream)))
 
 
 def occult_expert_ffn(cfg, plan, sfd_x, x, w_gate, w_up, w_down, epd_h, epd_y, h_shared=None,

@@ -58,9 +58,40 @@ __global__ __launch_bounds__(kDispWaves * 64) void dispatch_kernel_long(
   }
 }
 
+// routing metadata of every dispatched row: one thread per (token, device, slot)
+__global__ __launch_bounds__(256) void dispatch_meta_kernel(const int32_t* __restrict__ ids, const float* __restrict__ w,
+                                                            const int32_t* __restrict__ tok_sfd_row, int T, int D, int k,
+                                                            int32_t* __restrict__ sfd_ids, float* __restrict__ sfd_w) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)T * D * k) return;
+  const int s = (int)(i % k);
+  const size_t td = i / k;   // token * D + device
+  const int r = tok_sfd_row[td];
+  if (r < 0) return;
+  const size_t t = td / D;
+  sfd_ids[(size_t)r * k + s] = ids[t * k + s];
+  sfd_w[(size_t)r * k + s] = w[t * k + s];
+}
+
 }  // namespace occult
 
 using namespace occult;
+
+extern "C" int occult_dispatch_meta(const occult_cfg_t* cfg, const occult_plan_t* plan, const int32_t* ids,
+                                    const float* w, int32_t* sfd_ids, float* sfd_w, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  if (c.T == 0) return OCCULT_OK;
+  OCC_REQUIRE(plan && plan->tok_sfd_row, OCCULT_ENULLPTR, "plan or plan->tok_sfd_row is NULL");
+  OCC_REQUIRE(ids && w && sfd_ids && sfd_w, OCCULT_ENULLPTR, "ids, w, sfd_ids or sfd_w is NULL");
+  const size_t n = (size_t)c.T * c.D * c.k;
+  OCC_REQUIRE((n + 255) / 256 < (1ull << 31), OCCULT_EINVAL, "T*D*k too large for one launch");
+  hipLaunchKernelGGL(dispatch_meta_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), ids, w, plan->tok_sfd_row, c.T, c.D, c.k, sfd_ids, sfd_w);
+  OCC_LAUNCH_CHECK("dispatch_meta_kernel");
+  return OCCULT_OK;
+}
 
 extern "C" int occult_dispatch(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* x,
                                void* sfd_x, occult_stream_t stream) {

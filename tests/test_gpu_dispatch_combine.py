@@ -121,3 +121,33 @@ def test_combine_random_values_against_two_stage_oracle(dtype, S):
     else:
         assert f32_rel_error(got_sfd, sfd_ref) <= 1e-5
         assert f32_rel_error(got_y, y_ref) <= 1e-5
+
+
+META_CASES = [(16, 4, 4, 211, "random"), (60, 4, 4, 128, "contig"), (64, 8, 8, 4099, "random"),
+              (64, 64, 8, 300, "contig"), (8, 2, 2, 1, "contig")]
+
+
+@pytest.mark.parametrize("E,D,k,T,placement", META_CASES)
+def test_dispatch_meta_bit_exact(E, D, k, T, placement):
+    """ids and w of every dispatched row equal the oracle's (App. A.2: they travel with the row)."""
+    from paper_2505_13345_amd import binding as B
+    say(f"dispatch meta case E={E} D={D} k={k} T={T} {placement}")
+    dev = require_gpu()
+    lg = wl.random_logits(T, E, seed=T + E)
+    pos = None if placement == "contig" else wl.random_placement(E, D, seed=E)
+    pos_arr = wl.contiguous_placement(E, D) if pos is None else pos
+    ids, w = routing.route(lg, k, D, pos)
+    w32 = w.astype(np.float32)
+    layer = OccultLayer(T, 64, 64, E, 0, k, D, "bf16", expert_pos=pos, with_ffn=False)
+    ids_d, w_d = torch.from_numpy(ids).to(dev), torch.from_numpy(w32).to(dev)
+    layer.make_plan(ids_d, w_d)
+    rows = T * min(k, D)
+    sfd_ids = torch.full((rows, k), -7, dtype=torch.int32, device=dev)
+    sfd_w = torch.full((rows, k), -7.0, dtype=torch.float32, device=dev)
+    B.occult_dispatch_meta(layer.cfg, layer.plan, ids_d, w_d, sfd_ids, sfd_w)
+    torch.cuda.synchronize()
+    trace = occult_ref.moe_forward(np.zeros((T, 8)), ids, w32, pos_arr, D)
+    n = trace.n_sfd
+    assert np.array_equal(sfd_ids[:n].cpu().numpy(), trace.ids_sfd)
+    assert np.array_equal(sfd_w[:n].cpu().numpy(), trace.w_sfd)
+    assert bool((sfd_ids[n:] == -7).all()) and bool((sfd_w[n:] == -7.0).all())   # nothing past N_sfd
