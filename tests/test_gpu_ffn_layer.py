@@ -36,6 +36,11 @@ SMALL = [
     ("bf16_shared", 333, 512, 320, 12, 2, 3, 3, "bf16"),
     ("bf16_one_row_experts", 9, 128, 64, 16, 1, 2, 8, "bf16"),
     ("bf16_big_expert", 1500, 192, 448, 4, 0, 1, 2, "bf16"),
+    # ~20 rows per expert (weight-streaming kernel, some experts over 32 rows = two row tiles, some
+    # empty), shared experts as uniform groups of the small-tile kernel
+    ("bf16_few_rows_ragged", 80, 256, 192, 16, 2, 4, 4, "bf16"),
+    # 256-row tiles with three K tiles, shared experts as uniform groups of the same kernel
+    ("bf16_big_shared", 1100, 192, 128, 4, 3, 1, 4, "bf16"),
 ]
 
 
