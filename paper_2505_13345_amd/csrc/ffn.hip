@@ -682,7 +682,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     // K step 0 of the output tile: B half of K tile 1, fragments of step 1, products into zero
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-      load_b(b_off, w_lo, w_hi, kb_next, par ^ 1, g);
+      if ((g & 1) == 0) load_b(b_off, w_lo, w_hi, kb_next, par ^ 1, g >> 1);
       read_frag(1, par, 1, g);
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
@@ -691,12 +691,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    kb_advance();
 
     // steps 1 and 2 of K tile kt in stage s
-    auto steps_12 = [&](int s) {
+    auto steps_12 = [&](int s, const unsigned (&bo)[8], const char* lo, const char* hi, long long kb) {
 #pragma unroll
       for (int g = 0; g < 8; ++g) {
+        if ((g & 1) == 0) load_b(bo, lo, hi, kb, s ^ 1, 4 + (g >> 1));   // second half of the B loads begun in the step before
         read_frag(0, s, 2, g);
         mfma_pair(1, g);
         __builtin_amdgcn_sched_barrier(0);
@@ -712,7 +712,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     // K tiles 0 .. nk-3: steps 1, 2, wait for K tile kt+1, step 3, step 0 of K tile kt+1
     for (int kt = 0; kt < nk - 2; ++kt) {
       const int s = (par + kt) & 1;
-      steps_12(s);
+      steps_12(s, b_off, w_lo, w_hi, kb_next);
+      kb_advance();
       // K tile kt+1 has landed (this wave's loads, then every wave's), and every wave has issued
       // and completed its last reads of stage s, which may therefore be refilled
       wait_all_and_barrier();
@@ -725,17 +726,16 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       }
 #pragma unroll
       for (int g = 0; g < 8; ++g) {   // step 0 of K tile kt+1: B half of K tile kt+2 -> stage s
-        load_b(b_off, w_lo, w_hi, kb_next, s, g);
+        if ((g & 1) == 0) load_b(b_off, w_lo, w_hi, kb_next, s, g >> 1);
         read_frag(1, s ^ 1, 1, g);
         mfma_pair(0, g);
         __builtin_amdgcn_sched_barrier(0);
       }
-      kb_advance();
     }
 
     // K tile nk-2: as above, but the stage it frees receives K tile 0 of the next output tile
     const int s = (par + nk - 2) & 1, s1 = s ^ 1;
-    steps_12(s);
+    steps_12(s, b_off, w_lo, w_hi, kb_next);
     wait_all_and_barrier();
     unsigned na_off[8], nb_off[8];
     offsets_of(hn, na_off, nb_off);   // the gather has long landed: nothing is outstanding here
@@ -751,7 +751,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     }
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-      load_b(nb_off, nw_lo, nw_hi, 0, s, g);
+      if ((g & 1) == 0) load_b(nb_off, nw_lo, nw_hi, 0, s, g >> 1);
       read_frag(1, s1, 1, g);
       mfma_pair(0, g);
       __builtin_amdgcn_sched_barrier(0);
@@ -759,7 +759,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     // K tile nk-1 (stage s1): steps 1, 2; then the next tile's K tile 0 is complete in stage s and
     // stage s1 is free: step 3 sends the A half of the next tile's K tile 1 there and reads the
     // next tile's first fragments
-    steps_12(s1);
+    steps_12(s1, nb_off, nw_lo, nw_hi, 0);
     wait_all_and_barrier();
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
