@@ -37,6 +37,22 @@ Readings where the paper is silent:
 Gate *values* are computed in float64 from the float32 scores (the definition);
 only decisions use exp_ref.
 
+Expert-similarity-based pruning (Section 3.3, second criterion; Appendix "Similarity Table
+Construction") is ``prune_mode=3``.  The table comes from profiled router scores H [N, E]:
+squared cosine similarity of the expert columns, T2[i,j] = <H_i,H_j>^2 / (|H_i|^2 |H_j|^2)
+(`similarity`), which only needs the Gram matrix H^T H, summed over batches (`gram`).  Readings:
+* the integer table lists, for every expert i, the other experts by descending T2 (equal values ->
+  lower expert index first): `similarity_table` ([E, E-1]);
+* the devices that survive are found as in mode 2 (walk the top-k in descending score, keep the
+  first n_d distinct devices);
+* then the k routed experts are walked in descending score: an expert on a surviving device
+  stays in its slot; any other is replaced by the first expert of its table row that sits on a
+  surviving device and is not selected - where "selected" covers every routed expert that stays
+  (also those later in the walk) and the replacements made so far, so the result is k distinct
+  experts;
+* gates are the softmax values of the final experts (their own scores), renormalised if asked;
+  slots keep the walk order, so after a replacement slot order is no longer score order.
+
 Router scores themselves (Eq. 1: g is a single linear projection of the hidden
 state) are `router_scores`: the plain product x W_r^T in float64 from the stored
 inputs.  A second implementation of that product sums in another order, so its
@@ -114,10 +130,11 @@ def device_sums_mode1(logits: np.ndarray, ids0: np.ndarray, expert_device: np.nd
 
 
 def route(logits: np.ndarray, k: int, D: int, expert_pos: np.ndarray | None = None,
-          n_d: int = 0, prune_mode: int = 1, renorm: int = 1):
+          n_d: int = 0, prune_mode: int = 1, renorm: int = 1, sim_table: np.ndarray | None = None):
     """Return (ids [T,k] int32, w [T,k] float64).
 
     expert_pos[e] is expert e's placement position; its device is pos // (E/D).
+    sim_table [E, E-1] is the similarity table of prune_mode 3.
     """
     logits = np.ascontiguousarray(logits, dtype=np.float32)
     T, E = logits.shape
@@ -130,7 +147,7 @@ def route(logits: np.ndarray, k: int, D: int, expert_pos: np.ndarray | None = No
     ids = _topk_rows(logits, k)
     if n_d and n_d > 0:
         assert n_d * G >= k, "pruned range must hold k experts"
-        assert prune_mode in (1, 2)
+        assert prune_mode in (1, 2, 3)
         if prune_mode == 1:
             sums = device_sums_mode1(logits, ids, expert_device, D)
             kept_idx = _topk_rows(sums, n_d)            # highest sums, ties -> lower device
@@ -144,15 +161,67 @@ def route(logits: np.ndarray, k: int, D: int, expert_pos: np.ndarray | None = No
                 new = ~kept[np.arange(T), dev] & (n_kept < n_d)
                 kept[np.arange(T)[new], dev[new]] = True
                 n_kept += new
-        allowed = kept[:, expert_device]                # [T, E]
-        masked = np.where(allowed, logits, np.float32(-np.inf)).astype(np.float32)
-        ids = _topk_rows(masked, k)
+        if prune_mode == 3:
+            assert sim_table is not None and sim_table.shape == (E, E - 1)
+            ids = np.array([_replace_by_similarity(ids[t], kept[t], expert_device, sim_table)
+                            for t in range(T)], dtype=np.int32).reshape(T, k)
+        else:
+            allowed = kept[:, expert_device]                # [T, E]
+            masked = np.where(allowed, logits, np.float32(-np.inf)).astype(np.float32)
+            ids = _topk_rows(masked, k)
 
     p = softmax64(logits)
     w = np.take_along_axis(p, ids.astype(np.int64), axis=1)
     if renorm:
         w = w / w.sum(axis=1, keepdims=True)
     return ids, w
+
+
+def gram(logits: np.ndarray) -> np.ndarray:
+    """H^T H of profiled router scores H [N, E] in float64 (batches add up)."""
+    h = np.asarray(logits, dtype=np.float64)
+    return h.T @ h
+
+
+def similarity(g: np.ndarray) -> np.ndarray:
+    """Squared cosine similarity of expert columns from their Gram matrix:
+    T2[i,j] = g[i,j]^2 / (g[i,i] * g[j,j]), each operation rounded in float64 in this order."""
+    g = np.asarray(g, dtype=np.float64)
+    dg = np.diag(g)
+    return (g * g) / (dg[:, None] * dg[None, :])
+
+
+def similarity_table(g: np.ndarray) -> np.ndarray:
+    """[E, E-1] int32: row i lists the experts j != i by descending T2[i,j], equal -> lower j first."""
+    t2 = similarity(g)
+    E = t2.shape[0]
+    out = np.empty((E, E - 1), dtype=np.int32)
+    for i in range(E):
+        others = [j for j in range(E) if j != i]
+        others.sort(key=lambda j: (-t2[i, j], j))
+        out[i] = others
+    return out
+
+
+def _replace_by_similarity(ids_row, kept_dev, expert_device, table):
+    """One token of prune_mode 3: ids_row in descending score order -> final ids in walk order."""
+    stays = [int(e) for e in ids_row if kept_dev[expert_device[e]]]
+    selected = set(stays)
+    out = []
+    for e in ids_row:
+        e = int(e)
+        if kept_dev[expert_device[e]]:
+            out.append(e)
+            continue
+        for c in table[e]:
+            c = int(c)
+            if kept_dev[expert_device[c]] and c not in selected:
+                selected.add(c)
+                out.append(c)
+                break
+        else:
+            raise AssertionError("no replacement available: n_d * G < k?")
+    return out
 
 
 def router_scores(x: np.ndarray, w_router: np.ndarray) -> np.ndarray:

@@ -209,3 +209,105 @@ def test_selection_margin_bounds_what_a_perturbation_can_change():
         ids1, _ = routing.route(lg + noise, k, 4)
         changed = np.any(ids0 != ids1, axis=1)
         assert np.all(margin[changed] <= 2 * eps + 1e-6)
+
+
+# ---- expert-similarity-based pruning (Section 3.3, second criterion; similarity table appendix) ----
+
+def test_similarity_is_squared_cosine_of_columns():
+    rng = np.random.default_rng(2)
+    h = rng.standard_normal((300, 6))
+    h[:, 3] = -2.5 * h[:, 1]                 # anti-parallel columns count as identical (the square)
+    h[:, 5] = h[:, 0] - (h[:, 0] @ h[:, 2]) / (h[:, 2] @ h[:, 2]) * h[:, 2]   # orthogonal to column 2
+    t2 = routing.similarity(routing.gram(h))
+    for i in range(6):
+        for j in range(6):
+            cos = (h[:, i] @ h[:, j]) / (np.linalg.norm(h[:, i]) * np.linalg.norm(h[:, j]))
+            assert abs(t2[i, j] - cos * cos) < 1e-12
+    assert np.allclose(np.diag(t2), 1.0) and np.allclose(t2, t2.T)
+    assert abs(t2[1, 3] - 1.0) < 1e-12 and t2[2, 5] < 1e-20
+    # batches add up; rescaling an expert's scores changes nothing
+    g2 = routing.gram(h[:100]) + routing.gram(h[100:])
+    assert np.allclose(g2, routing.gram(h), rtol=1e-13)
+    assert np.allclose(routing.similarity(routing.gram(h * np.array([1, 7, 1, .1, 3, 1.]))), t2, rtol=1e-12, atol=1e-30)
+
+
+def test_similarity_table_rows_are_sorted_and_complete():
+    rng = np.random.default_rng(4)
+    h = rng.standard_normal((200, 9))
+    h[:, 7] = h[:, 4]                          # an exact tie for everybody: 4 before 7
+    g = routing.gram(h)
+    tab = routing.similarity_table(g)
+    t2 = routing.similarity(g)
+    assert tab.shape == (9, 8)
+    for i in range(9):
+        assert sorted(tab[i].tolist()) == [j for j in range(9) if j != i]
+        vals = t2[i, tab[i]]
+        assert np.all(vals[:-1] >= vals[1:])
+        for a, b in zip(tab[i][:-1], tab[i][1:]):
+            if t2[i, a] == t2[i, b]:
+                assert a < b
+    assert tab[4][0] == 7 and tab[7][0] == 4
+    pos4, pos7 = list(tab[0]).index(4), list(tab[0]).index(7)
+    assert pos7 == pos4 + 1
+
+
+def _route3_brute(logits, k, D, pos, n_d, t2):
+    """Mode 3 for one batch without the table: kept devices by the walk, replacements by a direct
+    arg-max of the similarity over the experts that are allowed and free."""
+    T, E = logits.shape
+    G = E // D
+    dev = [int(pos[e]) // G for e in range(E)]
+    out = []
+    for t in range(T):
+        order = sorted(range(E), key=lambda e: (-float(logits[t, e]), e))[:k]
+        kept = []
+        for e in order:
+            if dev[e] not in kept and len(kept) < n_d:
+                kept.append(dev[e])
+        taken = {e for e in order if dev[e] in kept}
+        final = []
+        for e in order:
+            if dev[e] in kept:
+                final.append(e)
+                continue
+            cands = [c for c in range(E) if c != e and dev[c] in kept and c not in taken]
+            best = min(cands, key=lambda c: (-t2[e, c], c))
+            taken.add(best)
+            final.append(best)
+        out.append(final)
+    return np.array(out, dtype=np.int32)
+
+
+@pytest.mark.parametrize("E,D,k,n_d,seed", [(8, 4, 3, 2, 0), (12, 3, 4, 1, 1), (16, 4, 4, 2, 2), (6, 3, 2, 1, 3),
+                                            (16, 8, 6, 3, 4)])
+def test_similarity_pruning_against_direct_search(E, D, k, n_d, seed):
+    rng = np.random.default_rng(seed)
+    T = 150
+    lg = rng.standard_normal((T, E)).astype(np.float32)
+    prof = rng.standard_normal((500, E)) + rng.standard_normal((500, 1))   # profiling scores, correlated columns
+    g = routing.gram(prof)
+    tab = routing.similarity_table(g)
+    pos = wl.random_placement(E, D, seed=seed + 10)
+    ids, w = routing.route(lg, k, D, pos, n_d=n_d, prune_mode=3, renorm=1, sim_table=tab)
+    assert np.array_equal(ids, _route3_brute(lg, k, D, pos, n_d, routing.similarity(g)))
+    G = E // D
+    ids0, _ = routing.route(lg, k, D, pos)
+    ids2, _ = routing.route(lg, k, D, pos, n_d=n_d, prune_mode=2)
+    p = routing.softmax64(lg)
+    for t in range(T):
+        assert len(set(ids[t].tolist())) == k                                   # k distinct experts
+        devs = set((pos[ids[t]] // G).tolist())
+        assert len(devs) <= n_d                                                 # at most n_d devices
+        kept_devs = set((pos[ids2[t]] // G).tolist())                           # same walk as mode 2
+        assert devs <= kept_devs
+        for s in range(k):                                                      # survivors keep their slot
+            if (pos[ids0[t, s]] // G) in kept_devs:
+                assert ids[t, s] == ids0[t, s]
+        if len(set((pos[ids0[t]] // G).tolist())) <= n_d:                       # nothing to prune: unchanged
+            assert np.array_equal(ids[t], ids0[t])
+        assert abs(w[t].sum() - 1.0) < 1e-12
+        assert np.allclose(w[t], p[t, ids[t]] / p[t, ids[t]].sum(), rtol=1e-12)  # gates = own softmax values
+    # a range that cannot prune anything leaves routing as it was
+    ids_all, w_all = routing.route(lg, k, D, pos, n_d=min(k, D), prune_mode=3, sim_table=tab)
+    ids_ref, w_ref = routing.route(lg, k, D, pos)
+    assert np.array_equal(ids_all, ids_ref) and np.allclose(w_all, w_ref)
