@@ -68,7 +68,12 @@ typedef struct occult_cfg {
                          use at most n_d devices, 1..D, and n_d * (E/D) >= k                */
   int32_t prune_mode; /* 1 = keep the n_d devices of highest summed gate score over the
                          token's unpruned top-k; 2 = keep the first n_d distinct devices met
-                         walking the unpruned top-k in descending score (Sec. 3.3 wording)  */
+                         walking the unpruned top-k in descending score (Sec. 3.3 wording);
+                         3 = expert-similarity-based pruning (Sec. 3.3): devices as in mode 2,
+                         then every routed expert outside them is replaced, walking the top-k
+                         in descending score, by the first expert of its row of sim_table that
+                         sits on a kept device and is neither a routed expert that stays nor an
+                         earlier replacement; slots keep the walk order                      */
   int32_t renorm;     /* 1 = gates divided by their sum over the selected k                 */
   int32_t dtype;      /* OCCULT_F32 or OCCULT_BF16: element type of x, weights, sfd, epd, y  */
   int32_t ffn_phase;  /* occult_expert_ffn only: 0 = both products; 1 = only the first (gate/up
@@ -76,6 +81,9 @@ typedef struct occult_cfg {
                          projection -> epd_y, y_shared).  For pipelining and per-kernel timing.  */
   const int32_t* expert_pos; /* device ptr [E]: placement position of each expert
                                 (device = pos / G, slot = pos % G); NULL = contiguous, pos[e] = e */
+  const int32_t* sim_table;  /* device ptr [E][E-1], read by occult_route when n_d > 0 and
+                                prune_mode == 3: row i = the other experts by descending
+                                similarity to i (occult_similarity_table); else may be NULL     */
 } occult_cfg_t;
 
 /* Dispatch plan: device tables, caller-allocated (one block of occult_plan_sizes() bytes carved
@@ -139,6 +147,19 @@ int occult_plan_bind(const occult_cfg_t* cfg, void* plan_mem, size_t plan_bytes,
  * restricted to n_d devices as described at occult_cfg.  cfg.expert_pos is read when n_d > 0. */
 int occult_route(const occult_cfg_t* cfg, const float* logits, int32_t* ids, float* w,
                  occult_stream_t stream);
+
+/* Expert similarity for prune_mode 3 (paper App. "Similarity Table Construction"): the table is
+ * built from profiled router scores H [N][E] through their Gram matrix H^T H.
+ * occult_similarity_gram adds (accumulate != 0) or writes the Gram matrix of logits [T][E] f32
+ * into gram [E][E] f64 (device ptrs), so that batches accumulate; sums run in double precision
+ * with atomic adds, so the last bits depend on the order the blocks finish in.
+ * occult_similarity_table (host, pure) turns a Gram matrix (host ptr [E][E] f64) into the integer
+ * table (host ptr [E][E-1] i32): row i lists the experts j != i by descending
+ * (g[i][j]*g[i][j]) / (g[i][i]*g[j][j]), equal values -> lower j first.  Copy it to the device
+ * and pass it as cfg.sim_table.  Needs E >= 2 and a positive diagonal. */
+int occult_similarity_gram(const occult_cfg_t* cfg, const float* logits, double* gram, int accumulate,
+                           occult_stream_t stream);
+int occult_similarity_table(const double* gram_host, int32_t E, int32_t* table_host);
 
 /* Router projection, then routing, in one call (paper Eq. 1: g(x) is a single linear projection of the
  * hidden state, followed by Softmax and top-k as in occult_route).  x [T][d] and w_router [E][d]

@@ -22,6 +22,7 @@ EXPORTS = [
     "occult_version", "occult_last_error", "occult_plan_sizes", "occult_plan_bind", "occult_route",
     "occult_plan", "occult_dispatch", "occult_expert_ffn", "occult_combine", "occult_coactivation",
     "occult_placement_greedy", "occult_plan_stats", "occult_router", "occult_dispatch_meta",
+    "occult_similarity_gram", "occult_similarity_table",
 ]
 
 
@@ -35,7 +36,7 @@ class occult_cfg_t(Structure):
     _fields_ = [("T", c_int32), ("d", c_int32), ("f", c_int32), ("E", c_int32), ("S", c_int32),
                 ("k", c_int32), ("D", c_int32), ("n_d", c_int32), ("prune_mode", c_int32),
                 ("renorm", c_int32), ("dtype", c_int32), ("ffn_phase", c_int32),
-                ("expert_pos", c_void_p)]
+                ("expert_pos", c_void_p), ("sim_table", c_void_p)]
 
 
 class occult_plan_t(Structure):
@@ -76,6 +77,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_plan_sizes.argtypes = [cfgp, POINTER(c_size_t), POINTER(c_size_t)]
     lib.occult_plan_bind.argtypes = [cfgp, c_void_p, c_size_t, planp]
     lib.occult_route.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.occult_similarity_gram.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
+    lib.occult_similarity_table.argtypes = [c_void_p, c_int32, c_void_p]
     lib.occult_router.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_plan.argtypes = [cfgp, c_void_p, c_void_p, planp, c_void_p, c_size_t, c_void_p]
     lib.occult_dispatch.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p]
@@ -110,10 +113,12 @@ def _stream(stream) -> Optional[int]:
     return stream.cuda_stream or None
 
 
-def make_cfg(T, d, f, E, S, k, D, dtype, n_d=0, prune_mode=1, renorm=1, expert_pos=None) -> occult_cfg_t:
-    """expert_pos: int32 device tensor [E] or None; the caller keeps it alive."""
+def make_cfg(T, d, f, E, S, k, D, dtype, n_d=0, prune_mode=1, renorm=1, expert_pos=None,
+             sim_table=None) -> occult_cfg_t:
+    """expert_pos: int32 device tensor [E] or None; sim_table: int32 device tensor [E, E-1] or None;
+    the caller keeps both alive."""
     code = {"bf16": OCCULT_BF16, "f32": OCCULT_F32}[dtype] if isinstance(dtype, str) else int(dtype)
-    return occult_cfg_t(T, d, f, E, S, k, D, n_d, prune_mode, renorm, code, 0, _ptr(expert_pos))
+    return occult_cfg_t(T, d, f, E, S, k, D, n_d, prune_mode, renorm, code, 0, _ptr(expert_pos), _ptr(sim_table))
 
 
 def occult_version() -> int:
@@ -140,6 +145,22 @@ def occult_plan_bind(cfg: occult_cfg_t, plan_mem) -> occult_plan_t:
 
 def occult_route(cfg, logits, ids, w, stream=None) -> None:
     _check(load_library().occult_route(ctypes.byref(cfg), _ptr(logits), _ptr(ids), _ptr(w), _stream(stream)))
+
+
+def occult_similarity_gram(cfg, logits, gram, accumulate=False, stream=None) -> None:
+    _check(load_library().occult_similarity_gram(ctypes.byref(cfg), _ptr(logits), _ptr(gram), int(bool(accumulate)),
+                                                 _stream(stream)))
+
+
+def occult_similarity_table(gram_host):
+    """Host: Gram matrix (numpy float64 [E, E]) -> similarity table (numpy int32 [E, E-1])."""
+    import numpy as np
+    g = np.ascontiguousarray(gram_host, dtype=np.float64)
+    E = g.shape[0]
+    out = np.empty((E, max(E - 1, 0)), dtype=np.int32)
+    _check(load_library().occult_similarity_table(g.ctypes.data_as(ctypes.c_void_p), E,
+                                                  out.ctypes.data_as(ctypes.c_void_p)))
+    return out
 
 
 def occult_router(cfg, x, w_router, logits, ids, w, stream=None) -> None:

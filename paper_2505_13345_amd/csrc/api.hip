@@ -30,7 +30,7 @@ int check_cfg(const occult_cfg_t* cfg) {
   OCC_REQUIRE(c.dtype == OCCULT_F32 || c.dtype == OCCULT_BF16, OCCULT_EINVAL, "unknown dtype %d", c.dtype);
   OCC_REQUIRE(c.n_d >= 0 && c.n_d <= c.D, OCCULT_EINVAL, "n_d=%d outside 0..D=%d", c.n_d, c.D);
   if (c.n_d > 0) {
-    OCC_REQUIRE(c.prune_mode == 1 || c.prune_mode == 2, OCCULT_EINVAL, "prune_mode=%d must be 1 or 2",
+    OCC_REQUIRE(c.prune_mode >= 1 && c.prune_mode <= 3, OCCULT_EINVAL, "prune_mode=%d must be 1, 2 or 3",
                 c.prune_mode);
     OCC_REQUIRE((int64_t)c.n_d * (c.E / c.D) >= c.k, OCCULT_ESHAPE,
                 "n_d=%d devices of %d experts cannot hold k=%d experts", c.n_d, c.E / c.D, c.k);

@@ -65,7 +65,8 @@ constexpr int kRouteWavesPerBlock = 4;
 // s_dev[e] is the device of expert e.  Lane s < k writes slot s.
 template <int EPL>  // experts per lane = ceil(E / 64)
 __device__ __forceinline__ void route_one(const float* row, int lane, int E, int k, int D, const int* s_dev,
-                                          int n_d, int prune_mode, int renorm, int32_t* ids_t, float* w_t) {
+                                          int n_d, int prune_mode, int renorm, const int32_t* sim_table,
+                                          int32_t* ids_t, float* w_t) {
   const float kNegInf = -INFINITY;
   float v0[EPL];   // the token's scores as read (with -0.0 folded onto +0.0)
   float v[EPL];    // working copy: taken / disallowed entries become -inf
@@ -122,7 +123,55 @@ __device__ __forceinline__ void route_one(const float* row, int lane, int E, int
     }
   }
 
-  if (n_d > 0) {
+  if (n_d > 0 && prune_mode == 3) {
+    // Expert-similarity-based pruning: routed experts on kept devices stay in their slots; the
+    // others are replaced, in slot (= descending score) order, by the first entry of their table
+    // row that is on a kept device and not taken.  `taken` = one bit per expert, wave-uniform.
+    unsigned long long taken[4] = {0ull, 0ull, 0ull, 0ull};
+    for (int s = 0; s < k; ++s) {
+      const int e = __shfl(my_id, s, 64);
+      if ((kept >> s_dev[e]) & 1ull) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if ((e >> 6) == q) taken[q] |= 1ull << (e & 63);
+      }
+    }
+    for (int s = 0; s < k; ++s) {
+      const int e = __shfl(my_id, s, 64);
+      if ((kept >> s_dev[e]) & 1ull) continue;   // wave-uniform
+      const int32_t* trow = sim_table + (size_t)e * (E - 1);
+      int found = -1;
+      for (int base = 0; base < E - 1 && found < 0; base += 64) {
+        const int q = base + lane;
+        int c = 0;
+        bool ok = false;
+        if (q < E - 1) {
+          c = trow[q];
+          unsigned long long word = taken[0];
+#pragma unroll
+          for (int m = 1; m < 4; ++m)
+            if ((c >> 6) == m) word = taken[m];
+          ok = ((kept >> s_dev[c]) & 1ull) && !((word >> (c & 63)) & 1ull);
+        }
+        const unsigned long long hits = __ballot(ok);
+        if (hits) found = __shfl(c, __ffsll((long long)hits) - 1, 64);
+      }
+      // host checks n_d * G >= k, so a free expert on a kept device always exists
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if ((found >> 6) == q) taken[q] |= 1ull << (found & 63);
+      // its score sits in lane found % 64, register found / 64
+      float fv = v0[0];
+#pragma unroll
+      for (int i = 1; i < EPL; ++i)
+        if ((found >> 6) == i) fv = v0[i];
+      fv = __shfl(fv, found & 63, 64);
+      if (lane == s) {
+        my_id = found;
+        my_v = fv;
+      }
+    }
+  } else if (n_d > 0) {
     if (prune_mode == 1) {
       float sv = (lane < D) ? dev_sum : kNegInf;
       kept = 0;
@@ -173,7 +222,7 @@ template <int EPL>
 __global__ __launch_bounds__(kRouteWavesPerBlock * 64) void route_kernel(
     const float* __restrict__ logits, int T, int E, int k, int D, int G,
     const int32_t* __restrict__ expert_pos, int n_d, int prune_mode, int renorm,
-    int32_t* __restrict__ ids, float* __restrict__ w) {
+    const int32_t* __restrict__ sim_table, int32_t* __restrict__ ids, float* __restrict__ w) {
   __shared__ int s_dev[OCCULT_MAX_E];
   for (int e = threadIdx.x; e < E; e += blockDim.x)
     s_dev[e] = (expert_pos ? expert_pos[e] : e) / G;
@@ -182,8 +231,8 @@ __global__ __launch_bounds__(kRouteWavesPerBlock * 64) void route_kernel(
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * kRouteWavesPerBlock + (threadIdx.x >> 6);
   if (t >= T) return;   // whole wave leaves together; no barrier follows
-  route_one<EPL>(logits + (size_t)t * E, lane, E, k, D, s_dev, n_d, prune_mode, renorm, ids + (size_t)t * k,
-                 w + (size_t)t * k);
+  route_one<EPL>(logits + (size_t)t * E, lane, E, k, D, s_dev, n_d, prune_mode, renorm, sim_table,
+                 ids + (size_t)t * k, w + (size_t)t * k);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -318,9 +367,115 @@ __global__ __launch_bounds__(256) void router_f32_kernel(const float* __restrict
   logits[i] = acc;
 }
 
+// Gram matrix of router scores, H^T H in float64.  A block takes a slice of tokens and a 64 x 64
+// tile of the matrix: the two 64-column panels of its tokens go through LDS, every thread keeps a
+// 4 x 4 patch of sums, and the tile is added to the result with double atomics.
+constexpr int kGramTokens = 64;
+__global__ __launch_bounds__(256) void gram_kernel(const float* __restrict__ logits, int T, int E,
+                                                   int tokens_per_block, double* __restrict__ gram) {
+  __shared__ float pa[kGramTokens][65], pb[kGramTokens][65];
+  const int tiles = (E + 63) / 64;
+  const int ti = blockIdx.y / tiles, tj = blockIdx.y % tiles;
+  const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;   // patch rows ty*4.., columns tx*4..
+  double acc[4][4] = {};
+  const int t_begin = blockIdx.x * tokens_per_block;
+  const int t_end = min(T, t_begin + tokens_per_block);
+  for (int t0 = t_begin; t0 < t_end; t0 += kGramTokens) {
+    for (int i = threadIdx.x; i < kGramTokens * 64; i += 256) {
+      const int tt = i / 64, c = i % 64;
+      const int t = t0 + tt;
+      const int ea = ti * 64 + c, eb = tj * 64 + c;
+      pa[tt][c] = (t < t_end && ea < E) ? logits[(size_t)t * E + ea] : 0.0f;
+      pb[tt][c] = (t < t_end && eb < E) ? logits[(size_t)t * E + eb] : 0.0f;
+    }
+    __syncthreads();
+    for (int tt = 0; tt < kGramTokens; ++tt) {
+      double a[4], b[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        a[q] = (double)pa[tt][ty * 4 + q];
+        b[q] = (double)pb[tt][tx * 4 + q];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = acc[i][j] + a[i] * b[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int ei = ti * 64 + ty * 4 + i, ej = tj * 64 + tx * 4 + j;
+      if (ei < E && ej < E) atomicAdd(&gram[(size_t)ei * E + ej], acc[i][j]);
+    }
+}
+
+__global__ void fill_f64(double* p, size_t n, double v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
 }  // namespace occult
 
 using namespace occult;
+
+extern "C" int occult_similarity_gram(const occult_cfg_t* cfg, const float* logits, double* gram,
+                                      int accumulate, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  OCC_REQUIRE(gram, OCCULT_ENULLPTR, "gram is NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t n = (size_t)c.E * c.E;
+  if (!accumulate) {   // a fill kernel rather than a memset node, so the call can be captured in a graph
+    hipLaunchKernelGGL(fill_f64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, gram, n, 0.0);
+    OCC_LAUNCH_CHECK("fill_f64");
+  }
+  if (c.T == 0) return OCCULT_OK;
+  OCC_REQUIRE(logits, OCCULT_ENULLPTR, "logits is NULL");
+  const int tiles = (c.E + 63) / 64;
+  int slices = (c.T + 1023) / 1024;          // about 1024 tokens per block
+  if (slices < 1) slices = 1;
+  const int per = ((c.T + slices - 1) / slices + kGramTokens - 1) / kGramTokens * kGramTokens;
+  slices = (c.T + per - 1) / per;
+  hipLaunchKernelGGL(gram_kernel, dim3(slices, tiles * tiles), dim3(256), 0, s, logits, c.T, c.E, per, gram);
+  OCC_LAUNCH_CHECK("gram_kernel");
+  return OCCULT_OK;
+}
+
+extern "C" int occult_similarity_table(const double* gram_host, int32_t E, int32_t* table_host) {
+  OCC_REQUIRE(gram_host && table_host, OCCULT_ENULLPTR, "gram_host or table_host is NULL");
+  OCC_REQUIRE(E >= 2 && E <= OCCULT_MAX_E, OCCULT_EINVAL, "E=%d outside 2..%d", E, OCCULT_MAX_E);
+  for (int i = 0; i < E; ++i)
+    OCC_REQUIRE(gram_host[(size_t)i * E + i] > 0.0, OCCULT_EINVAL, "gram[%d][%d] is not positive", i, i);
+  double sim[OCCULT_MAX_E];
+  for (int i = 0; i < E; ++i) {
+    for (int j = 0; j < E; ++j) {
+      // each product and the quotient rounded on its own (file-wide contraction is off)
+      const double g = gram_host[(size_t)i * E + j];
+      const double num = g * g;
+      const double den = gram_host[(size_t)i * E + i] * gram_host[(size_t)j * E + j];
+      sim[j] = num / den;
+    }
+    int32_t* row = table_host + (size_t)i * (E - 1);
+    int n = 0;
+    for (int j = 0; j < E; ++j)
+      if (j != i) row[n++] = j;
+    // insertion sort by (similarity descending, index ascending): stable, E <= 256
+    for (int a = 1; a < n; ++a) {
+      const int32_t v = row[a];
+      int b = a - 1;
+      while (b >= 0 && sim[row[b]] < sim[v]) {
+        row[b + 1] = row[b];
+        --b;
+      }
+      row[b + 1] = v;
+    }
+  }
+  return OCCULT_OK;
+}
 
 extern "C" int occult_route(const occult_cfg_t* cfg, const float* logits, int32_t* ids, float* w,
                             occult_stream_t stream) {
@@ -329,13 +484,15 @@ extern "C" int occult_route(const occult_cfg_t* cfg, const float* logits, int32_
   const occult_cfg_t c = *cfg;
   if (c.T == 0) return OCCULT_OK;
   OCC_REQUIRE(logits && ids && w, OCCULT_ENULLPTR, "logits, ids or w is NULL");
+  if (c.n_d > 0 && c.prune_mode == 3)
+    OCC_REQUIRE(c.sim_table != nullptr, OCCULT_ENULLPTR, "prune_mode 3 needs cfg.sim_table");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int G = c.E / c.D;
   const dim3 grid((c.T + kRouteWavesPerBlock - 1) / kRouteWavesPerBlock), block(kRouteWavesPerBlock * 64);
   const int epl = (c.E + 63) / 64;
 #define OCC_ROUTE_LAUNCH(N)                                                                     \
   hipLaunchKernelGGL(route_kernel<N>, grid, block, 0, s, logits, c.T, c.E, c.k, c.D, G,         \
-                     c.expert_pos, c.n_d, c.prune_mode, c.renorm, ids, w)
+                     c.expert_pos, c.n_d, c.prune_mode, c.renorm, c.sim_table, ids, w)
   switch (epl) {
     case 1: OCC_ROUTE_LAUNCH(1); break;
     case 2: OCC_ROUTE_LAUNCH(2); break;

@@ -13,7 +13,7 @@ from . import binding as B
 
 class OccultLayer:
     def __init__(self, T, d, f, E, S, k, D, dtype="bf16", n_d=0, prune_mode=1, renorm=1,
-                 expert_pos=None, device="cuda:0", with_ffn=True):
+                 expert_pos=None, device="cuda:0", with_ffn=True, sim_table=None):
         B.load_library()          # fail early and loudly if the HIP library is missing
         self.device = torch.device(device)
         self.shape = dict(T=T, d=d, f=f, E=E, S=S, k=k, D=D)
@@ -23,7 +23,10 @@ class OccultLayer:
         self.expert_pos = None
         if expert_pos is not None:
             self.expert_pos = torch.as_tensor(expert_pos, dtype=torch.int32).to(dev).contiguous()
-        self.cfg = B.make_cfg(T, d, f, E, S, k, D, dtype, n_d, prune_mode, renorm, self.expert_pos)
+        self.sim_table = None
+        if sim_table is not None:
+            self.sim_table = torch.as_tensor(sim_table, dtype=torch.int32).to(dev).contiguous()
+        self.cfg = B.make_cfg(T, d, f, E, S, k, D, dtype, n_d, prune_mode, renorm, self.expert_pos, self.sim_table)
         plan_bytes, ws_bytes = B.occult_plan_sizes(self.cfg)
         self.plan_mem = torch.zeros(plan_bytes, dtype=torch.uint8, device=dev)
         self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)

@@ -43,7 +43,7 @@ def test_cfg_validation_reports_errors_without_a_gpu(lib):
         (dict(good, k=17), -1),           # k > E
         (dict(good, E=512, D=4), -1),     # E above the limit
         (dict(good, n_d=1, k=8), -2),     # pruned range cannot hold k
-        (dict(good, n_d=2, prune_mode=3), -1),
+        (dict(good, n_d=2, prune_mode=4), -1),
         (dict(good, T=-1), -1),
         (dict(good, renorm=2), -1),
     ]
@@ -58,6 +58,15 @@ def test_cfg_validation_reports_errors_without_a_gpu(lib):
     assert rc == -4
     rc = lib.occult_dispatch(ctypes.byref(cfg), None, None, None, None)
     assert rc == -4
+    # the host similarity-table builder: exact against the oracle, bad input refused
+    import numpy as np
+    from oracle import routing
+    h = np.random.default_rng(0).standard_normal((50, 7))
+    g = routing.gram(h)
+    assert np.array_equal(B.occult_similarity_table(g), routing.similarity_table(g))
+    g[3, 3] = 0.0
+    with pytest.raises(B.OccultError):
+        B.occult_similarity_table(g)
 
 
 def test_plan_bind_layout_is_aligned_and_disjoint(lib):

@@ -171,3 +171,60 @@ def test_coactivation_counts(E, k, T):
     B.occult_coactivation(cfg, ids_d, C, True)       # accumulate over a second batch
     torch.cuda.synchronize()
     assert np.array_equal(C.cpu().numpy(), 2 * C_ref)
+
+
+# ---- expert-similarity-based pruning (prune_mode 3) -------------------------------------------
+
+SIM_CASES = [
+    # E, D, k, T, n_d, renorm, placement
+    (16, 4, 4, 1000, 2, 1, "random"),
+    (60, 4, 4, 777, 1, 1, "contig"),
+    (64, 8, 8, 4099, 2, 1, "contig"),
+    (64, 8, 8, 2000, 3, 0, "random"),
+    (128, 8, 8, 1500, 2, 1, "random"),
+    (256, 16, 8, 900, 4, 1, "random"),
+    (8, 4, 2, 65, 1, 1, "contig"),
+]
+
+
+@pytest.mark.parametrize("E,D,k,T,n_d,renorm,placement", SIM_CASES)
+def test_similarity_pruning_matches_oracle(E, D, k, T, n_d, renorm, placement):
+    say(f"similarity pruning case E={E} D={D} k={k} T={T} n_d={n_d} {placement}")
+    dev = require_gpu()
+    prof = wl.random_logits(3000, E, seed=E + 1, scale=1.0)
+    prof = (prof + np.random.default_rng(E).standard_normal((3000, 1)).astype(np.float32)).astype(np.float32)
+    # Gram matrix on the GPU in two accumulated batches against the oracle's
+    cfg = B.make_cfg(2000, 64, 64, E, 0, k, D, "bf16")
+    gram = torch.full((E, E), 123.0, dtype=torch.float64, device=dev)
+    prof_d = torch.from_numpy(prof).to(dev)
+    B.occult_similarity_gram(cfg, prof_d[:2000].contiguous(), gram, accumulate=False)
+    cfg2 = B.make_cfg(1000, 64, 64, E, 0, k, D, "bf16")
+    B.occult_similarity_gram(cfg2, prof_d[2000:].contiguous(), gram, accumulate=True)
+    torch.cuda.synchronize()
+    g_gpu = gram.cpu().numpy()
+    g_ref = routing.gram(prof)
+    assert np.max(np.abs(g_gpu - g_ref)) <= 1e-11 * np.max(np.abs(g_ref))
+    # the host table builder is exact: same table as the oracle from the same Gram matrix
+    tab = B.occult_similarity_table(g_gpu)
+    assert np.array_equal(tab, routing.similarity_table(g_gpu))
+    # and from the oracle's Gram matrix the table may differ only where similarities are as good as equal
+    tab_ref = routing.similarity_table(g_ref)
+    if not np.array_equal(tab, tab_ref):
+        t2 = routing.similarity(g_ref)
+        i, q = np.argwhere(tab != tab_ref)[0]
+        assert abs(t2[i, tab[i, q]] - t2[i, tab_ref[i, q]]) <= 1e-10
+    # routing with that table
+    lg = wl.random_logits(T, E, seed=E * 5 + k, scale=1.3)
+    pos = None if placement == "contig" else wl.random_placement(E, D, seed=E + D)
+    ids_ref, w_ref = routing.route(lg, k, D, pos, n_d=n_d, prune_mode=3, renorm=renorm, sim_table=tab)
+    layer = OccultLayer(T, 64, 64, E, 0, k, D, "bf16", n_d, 3, renorm, pos, with_ffn=False, sim_table=tab)
+    layer.route(torch.from_numpy(lg).to(dev))
+    torch.cuda.synchronize()
+    ids, w = layer.ids.cpu().numpy(), layer.w.cpu().numpy()
+    assert np.array_equal(ids, ids_ref)
+    assert np.max(np.abs(w.astype(np.float64) - w_ref) / w_ref) <= 1e-5
+    # and the plan built on it keeps every token within n_d devices
+    layer.make_plan()
+    torch.cuda.synchronize()
+    mask = layer.tables()["tok_devmask"].cpu().numpy().astype(np.uint64)
+    assert max(bin(int(m)).count("1") for m in mask) <= n_d
