@@ -203,6 +203,18 @@ int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const 
                       const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
                       void* h_shared, void* y_shared, occult_stream_t stream);
 
+/* occult_expert_ffn with a scratch buffer.  For small batches (24 <= T < 192) with shared experts
+ * the shared down projection has few output tiles and a long K = S*f; given `ws` (device ptr,
+ * 16-byte aligned, >= occult_expert_ffn_ws_bytes() bytes) it is split over K into f32 partial
+ * sums that a second kernel adds in a fixed order and rounds once.  With ws == NULL, too few
+ * bytes, or a layer that does not need it (ws_bytes == 0), identical to occult_expert_ffn.
+ * The contents of ws are not kept between calls. */
+int occult_expert_ffn_ws_bytes(const occult_cfg_t* cfg, size_t* ws_bytes);
+int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                         const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
+                         void* h_shared, void* y_shared, void* ws, size_t ws_bytes,
+                         occult_stream_t stream);
+
 /* Two-stage combine (paper Sec. 3.1 two-stage aggregation of Eq. 0; App. A.2 "Weight
  * Modulation", the accumulation of "SMM with Merging", and "Combine").
  * Stage 1 (on the device, before the return trip): sfd_y[r] = sum over the EPD rows q of SFD

@@ -22,7 +22,7 @@ EXPORTS = [
     "occult_version", "occult_last_error", "occult_plan_sizes", "occult_plan_bind", "occult_route",
     "occult_plan", "occult_dispatch", "occult_expert_ffn", "occult_combine", "occult_coactivation",
     "occult_placement_greedy", "occult_plan_stats", "occult_router", "occult_dispatch_meta",
-    "occult_similarity_gram", "occult_similarity_table",
+    "occult_similarity_gram", "occult_similarity_table", "occult_expert_ffn_ws_bytes", "occult_expert_ffn_ws",
 ]
 
 
@@ -85,6 +85,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_dispatch_meta.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_expert_ffn.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t),
                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.occult_expert_ffn_ws_bytes.argtypes = [cfgp, POINTER(c_size_t)]
+    lib.occult_expert_ffn_ws.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t),
+                                         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.occult_combine.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_coactivation.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_placement_greedy.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
@@ -189,6 +192,21 @@ def occult_expert_ffn(cfg, plan, sfd_x, x, w_gate, w_up, w_down, epd_h, epd_y, h
     _check(load_library().occult_expert_ffn(ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x),
                                             ctypes.byref(wts), _ptr(epd_h), _ptr(epd_y), _ptr(h_shared),
                                             _ptr(y_shared), _stream(stream)))
+
+
+def occult_expert_ffn_ws_bytes(cfg) -> int:
+    n = c_size_t(0)
+    _check(load_library().occult_expert_ffn_ws_bytes(ctypes.byref(cfg), ctypes.byref(n)))
+    return int(n.value)
+
+
+def occult_expert_ffn_ws(cfg, plan, sfd_x, x, w_gate, w_up, w_down, epd_h, epd_y, h_shared, y_shared, ws,
+                         stream=None) -> None:
+    wts = occult_weights_t(_ptr(w_gate), _ptr(w_up), _ptr(w_down))
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().occult_expert_ffn_ws(ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x),
+                                               ctypes.byref(wts), _ptr(epd_h), _ptr(epd_y), _ptr(h_shared),
+                                               _ptr(y_shared), _ptr(ws), nbytes, _stream(stream)))
 
 
 def occult_combine(cfg, plan, epd_y, sfd_y, y_shared, y, stream=None) -> None:

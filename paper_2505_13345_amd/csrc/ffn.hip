@@ -39,6 +39,10 @@ struct GemmArgs {
   int ngroups;
   int M;                    // rows when grp_offset == NULL
   int a_rows_total;         // rows of the A buffer that may be addressed (bounds 32-bit offsets)
+  int plain_map;            // small-tile kernel: workgroup id = m-tile * n_tiles + n-tile (tiny grids)
+  int ksplit;               // small-tile kernel, one group, no SWIGLU: blockIdx.y takes K tiles
+                            // [y*nk/ksplit, (y+1)*nk/ksplit) and writes f32 sums to ws; 0 or 1 = off
+  float* ws;                // [ksplit][M][N] partial sums
   int N;                    // output columns (for SWIGLU: columns of h)
   int K;
 };
@@ -142,7 +146,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 
   constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
   const int n_tiles = (a.N + BN_OUT - 1) / BN_OUT;
-  const TileMap tm = map_tile(n_tiles);
+  TileMap tm = map_tile(n_tiles);
+  if (a.plain_map) {
+    tm.mt = blockIdx.x / n_tiles;
+    tm.nt = blockIdx.x % n_tiles;
+  }
   const int mt = tm.mt;
   const int n0 = tm.nt * BN_OUT;
   const TileInfo ti = find_tile<BM>(a, mt, &s_info);
@@ -187,7 +195,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.0f;
 
-  const int nk = a.K / BK;
+  const int nk_all = a.K / BK;
+  const int split = a.ksplit > 1 ? a.ksplit : 1;
+  const int kt_begin = (int)((long long)blockIdx.y * nk_all / split);   // this block's K tiles
+  const int nk = (int)((long long)(blockIdx.y + 1) * nk_all / split);   // (end, exclusive)
   // two K tiles are in flight in registers while a third is multiplied out of LDS
   u32x4 ga0[4], gb0[4], ga1[4], gb1[4];
   auto load_global = [&](int kt, u32x4 (&ga)[4], u32x4 (&gb)[4]) {
@@ -227,9 +238,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     }
     __syncthreads();
   };
-  load_global(0, ga0, gb0);
-  if (nk > 1) load_global(1, ga1, gb1);
-  for (int kt = 0; kt < nk; kt += 2) {
+  load_global(kt_begin, ga0, gb0);
+  if (kt_begin + 1 < nk) load_global(kt_begin + 1, ga1, gb1);
+  for (int kt = kt_begin; kt < nk; kt += 2) {
     k_tile(kt, ga0, gb0);
     if (kt + 1 < nk) k_tile(kt + 1, ga1, gb1);
   }
@@ -244,6 +255,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       const int row = ti.m0 + wm * 64 + mi * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
       if (row >= ti.rows) continue;
       __bf16* crow = C + (long long)(ti.row_base + row) * a.ldc + group_col0(a, ti.group);
+      if (!SWIGLU && a.ksplit > 1) {   // partial sums of this K slice, f32
+        float* prow = a.ws + ((long long)blockIdx.y * a.M + row) * a.N;
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) {
+          const int col = n0 + wn * 64 + ni * 32 + col_in;
+          if (col < a.N) prow[col] = acc[mi][ni][r];
+        }
+        continue;
+      }
       if (SWIGLU) {
         const int col = n0 + wn * 32 + col_in;
         if (col < a.N) {
@@ -937,6 +957,32 @@ static int device_cu_count(int* out) {
   return OCCULT_OK;
 }
 
+// sums the K slices of a split product in slice order and rounds once: out[row][col0 + col]
+__global__ __launch_bounds__(256) void splitk_reduce_bf16(const float* __restrict__ ws, int ksplit, int M, int N,
+                                                          __bf16* __restrict__ out, int ldc, int col0) {
+  const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;   // 4 columns per thread (N % 4 == 0)
+  if (i >= (size_t)M * N) return;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(ws + i);
+  for (int ks = 1; ks < ksplit; ++ks) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(ws + (size_t)ks * M * N + i);
+    sum = sum + v;
+  }
+  const size_t row = i / N, col = i % N;
+  uint2 pk;
+  pk.x = pack_bf16(sum.x, sum.y);
+  pk.y = pack_bf16(sum.z, sum.w);
+  *reinterpret_cast<uint2*>(out + row * ldc + col0 + col) = pk;
+}
+
+// K slices for a product whose tiles alone would leave most of the chip idle (0 = do not split)
+static int choose_ksplit(long long tiles, int nk) {
+  if (tiles >= 128 || nk < 8) return 0;
+  long long ks = 256 / tiles;
+  if (ks > nk / 4) ks = nk / 4;
+  if (ks > 8) ks = 8;
+  return ks >= 2 ? (int)ks : 0;
+}
+
 static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
   if (total_rows == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
@@ -970,13 +1016,28 @@ static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, in
       const long long resident = cus >= 8 ? cus / 8 * 8 : 8;
       if (blocks > resident) blocks = resident;
     }
-    const dim3 grid((unsigned)blocks), block(256);
+    const bool split = !use_big && !swiglu && a.ksplit > 1;   // caller set ksplit and ws (one group)
+    GemmArgs b = a;
+    if (!split) b.ksplit = 0;
+    // the XCD-aware order pads the grid to whole chunks per XCD: pointless when there are few tiles
+    const long long plain_blocks = m_tiles * ((a.N + bn_out - 1) / bn_out);
+    if (!use_big && plain_blocks <= 512) {
+      b.plain_map = 1;
+      blocks = plain_blocks;
+    }
+    const dim3 grid((unsigned)blocks, split ? (unsigned)b.ksplit : 1u), block(256);
     if (use_big) {
-      if (swiglu) hipLaunchKernelGGL(t256::grouped_gemm_bf16<true>, grid, block, 0, s, a);
-      else hipLaunchKernelGGL(t256::grouped_gemm_bf16<false>, grid, block, 0, s, a);
+      if (swiglu) hipLaunchKernelGGL(t256::grouped_gemm_bf16<true>, grid, block, 0, s, b);
+      else hipLaunchKernelGGL(t256::grouped_gemm_bf16<false>, grid, block, 0, s, b);
     } else {
-      if (swiglu) hipLaunchKernelGGL(small::grouped_gemm_bf16<true>, grid, block, 0, s, a);
-      else hipLaunchKernelGGL(small::grouped_gemm_bf16<false>, grid, block, 0, s, a);
+      if (swiglu) hipLaunchKernelGGL(small::grouped_gemm_bf16<true>, grid, block, 0, s, b);
+      else hipLaunchKernelGGL(small::grouped_gemm_bf16<false>, grid, block, 0, s, b);
+    }
+    if (split) {
+      OCC_LAUNCH_CHECK("grouped_gemm");
+      const size_t quads = (size_t)b.M * b.N / 4;
+      hipLaunchKernelGGL(splitk_reduce_bf16, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, b.ws, b.ksplit,
+                         b.M, b.N, static_cast<__bf16*>(b.C), b.ldc, b.c_col0);
     }
   } else {
     const long long m_tiles = (total_rows + FM - 1) / FM + a.ngroups;
@@ -996,9 +1057,31 @@ static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, in
 using namespace occult;
 
 
-extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
-                                 const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
-                                 void* h_shared, void* y_shared, occult_stream_t stream) {
+// Scratch that lets the shared experts' down projection of a small batch be split over K: the
+// product has T/128 x d/128 tiles only (16 for T = 128, d = 2048) with a long K = S*f.
+static size_t ffn_ws_need(const occult_cfg_t& c, int* ksplit_out) {
+  *ksplit_out = 0;
+  if (c.S == 0 || c.dtype != OCCULT_BF16 || c.T == 0) return 0;
+  if (c.T >= 192 || c.T < 24) return 0;   // those batches take the 256-row tiles / the weight-streaming kernel
+  const long long tiles = (long long)((c.T + 127) / 128) * ((c.d + 127) / 128);
+  const int ks = choose_ksplit(tiles, c.S * c.f / 64);
+  if (ks == 0 || c.d % 4 != 0) return 0;
+  *ksplit_out = ks;
+  return (size_t)ks * c.T * c.d * sizeof(float);
+}
+
+extern "C" int occult_expert_ffn_ws_bytes(const occult_cfg_t* cfg, size_t* ws_bytes) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  OCC_REQUIRE(ws_bytes, OCCULT_ENULLPTR, "ws_bytes is NULL");
+  int ks = 0;
+  *ws_bytes = ffn_ws_need(*cfg, &ks);
+  return OCCULT_OK;
+}
+
+static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                           const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
+                           void* h_shared, void* y_shared, void* ws, size_t ws_bytes, occult_stream_t stream) {
   int rc = check_cfg(cfg);
   if (rc) return rc;
   const occult_cfg_t c = *cfg;
@@ -1048,6 +1131,12 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
       a2.C = y_shared; a2.ldc = c.d; a2.c_col0 = 0;
       a2.grp_offset = nullptr; a2.grp_widx = nullptr; a2.w_base = c.E;
       a2.ngroups = 1; a2.M = c.T; a2.N = c.d; a2.K = c.S * c.f; a2.a_rows_total = c.T;
+      int ks = 0;
+      const size_t need = ffn_ws_need(c, &ks);
+      if (ks > 1 && ws != nullptr && ws_bytes >= need) {
+        a2.ksplit = ks;
+        a2.ws = static_cast<float*>(ws);
+      }
       return launch_gemm(c, a2, false, c.T, s_shared);
     }
     return OCCULT_OK;
@@ -1086,4 +1175,18 @@ extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* p
     if (rc) return rc;
   }
   return OCCULT_OK;
+}
+
+extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                 const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
+                                 void* h_shared, void* y_shared, occult_stream_t stream) {
+  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, epd_h, epd_y, h_shared, y_shared, nullptr, 0, stream);
+}
+
+extern "C" int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                    const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
+                                    void* h_shared, void* y_shared, void* ws, size_t ws_bytes,
+                                    occult_stream_t stream) {
+  if (ws != nullptr) OCC_REQUIRE(aligned16(ws), OCCULT_EALIGN, "ws is not 16-byte aligned");
+  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, epd_h, epd_y, h_shared, y_shared, ws, ws_bytes, stream);
 }

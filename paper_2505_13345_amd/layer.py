@@ -38,8 +38,11 @@ class OccultLayer:
         self.sfd_x = torch.zeros((n_sfd_max, d), dtype=self.tdtype, device=dev)
         self.sfd_y = torch.zeros((n_sfd_max, d), dtype=self.tdtype, device=dev)
         self.y = torch.zeros((T, d), dtype=self.tdtype, device=dev)
-        self.epd_h = self.epd_y = self.h_shared = self.y_shared = None
+        self.epd_h = self.epd_y = self.h_shared = self.y_shared = self.ffn_ws = None
         if with_ffn:
+            ws_bytes = B.occult_expert_ffn_ws_bytes(self.cfg)
+            if ws_bytes:
+                self.ffn_ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device=dev)
             self.epd_h = torch.zeros((T * k, f), dtype=self.tdtype, device=dev)
             self.epd_y = torch.zeros((T * k, d), dtype=self.tdtype, device=dev)
             if S > 0:
@@ -61,9 +64,13 @@ class OccultLayer:
     def dispatch(self, x):
         B.occult_dispatch(self.cfg, self.plan, x, self.sfd_x)
 
-    def expert_ffn(self, x, w_gate, w_up, w_down):
-        B.occult_expert_ffn(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h,
-                            self.epd_y, self.h_shared, self.y_shared)
+    def expert_ffn(self, x, w_gate, w_up, w_down, use_ws=True):
+        if use_ws and self.ffn_ws is not None:
+            B.occult_expert_ffn_ws(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h,
+                                   self.epd_y, self.h_shared, self.y_shared, self.ffn_ws)
+        else:
+            B.occult_expert_ffn(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h,
+                                self.epd_y, self.h_shared, self.y_shared)
 
     def combine(self, epd_y=None):
         B.occult_combine(self.cfg, self.plan, self.epd_y if epd_y is None else epd_y, self.sfd_y,

@@ -165,3 +165,37 @@ def test_large_config_sampled_with_greedy_placement():
     # placement never changes the layer output beyond rounding (exactness)
     mx, mean = bf16_errors(y2, y)
     assert mx <= 4e-2 and mean <= 2e-3
+
+
+def test_shared_down_projection_split_over_k_matches_unsplit():
+    """occult_expert_ffn_ws (K slices summed in f32, rounded once) against occult_expert_ffn on the
+    decode-shaped layer: the same numbers up to one bf16 rounding of differently ordered f32 sums,
+    and each within the bars of the oracle."""
+    shape = wl.CONFIGS["decode_bf16"]
+    say("decode_bf16 split-K: generating")
+    wk = wl.make_workload(shape)
+    dev = require_gpu()
+    layer = OccultLayer(shape.T, shape.d, shape.f, shape.E, shape.S, shape.k, shape.D, shape.dtype)
+    assert layer.ffn_ws is not None            # this shape asks for scratch
+    x = to_dev(wk.x, shape.dtype, dev)
+    wg, wu, wd = (to_dev(a, shape.dtype, dev) for a in (wk.w_gate, wk.w_up, wk.w_down))
+    layer.route(torch.from_numpy(wk.logits).to(dev)); layer.make_plan(); layer.dispatch(x)
+    outs = []
+    for use_ws in (False, True, True):          # twice with scratch: the buffer's old contents do not matter
+        layer.y_shared.fill_(7.0)
+        layer.expert_ffn(x, wg, wu, wd, use_ws=use_ws)
+        torch.cuda.synchronize()
+        outs.append(layer.y_shared.float().cpu().numpy().copy())
+    assert np.array_equal(outs[1], outs[2])
+    xs = wk.x.astype(np.float64)
+    ref = np.zeros((shape.T, shape.d))
+    for s_ in range(shape.S):
+        e = shape.E + s_
+        g = xs @ wk.w_gate[e].astype(np.float64).T
+        u = xs @ wk.w_up[e].astype(np.float64).T
+        ref += (g / (1.0 + np.exp(-g)) * u) @ wk.w_down[e].astype(np.float64).T
+    for o in outs[:2]:
+        mx, mean = bf16_errors(o, ref)
+        say(f"  shared experts: max-abs {mx:.3e} mean-abs {mean:.3e}")
+        assert mx <= 2e-2 and mean <= 2e-3
+    assert np.max(np.abs(outs[0] - outs[1])) <= 2e-2
