@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
     const void* __restrict__ epd_y, void* __restrict__ sfd_y, const void* __restrict__ y_shared,
     void* __restrict__ y, const int32_t* __restrict__ tok_sfd_row,
     const int32_t* __restrict__ sfd_epd_rows, const float* __restrict__ epd_gate, int T, int D, int M1,
-    int row_vecs) {
+    int row_vecs, int lists_fit) {
   using R = Row<BF16>;
   constexpr int NE = R::kElems;
   const int lane = threadIdx.x & 63;
@@ -79,9 +79,35 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
 #pragma unroll
       for (int e = 0; e < NE; ++e) acc[i][e] = 0.0f;
 
-    for (int j = 0; j < D; ++j) {
-      const int r = tok_sfd_row[(size_t)t * D + j];   // wave-uniform
-      if (r < 0) continue;
+    // The token's index lists in three wave-wide loads instead of one dependent load per entry
+    // (D <= 64 and, when lists_fit, min(k, D) * M1 <= 64): lane j reads the SFD row on device j,
+    // the rows are compacted in device order, lane (o, m) reads EPD row and gate m of the o-th one.
+    int n_dev = D, my_row = -1, my_q = -1;
+    float my_g = 0.0f;
+    if (lists_fit) {
+      const int rl = lane < D ? tok_sfd_row[(size_t)t * D + lane] : -1;
+      const unsigned long long present = __ballot(rl >= 0);
+      n_dev = __popcll(present);
+      const int ord = __popcll(present & ((1ull << lane) - 1ull));
+      // push each present row to lane `ord` (absent lanes push to lane 63 + their own, dropped by the mask below)
+      my_row = __builtin_amdgcn_ds_permute((rl >= 0 ? ord : 63) * 4, rl);
+      if (lane >= n_dev) my_row = -1;
+      const int o = lane / M1, m = lane - o * M1;
+      const int r_o = __shfl(my_row, o < 64 ? o : 0, 64);
+      if (o < n_dev) {
+        my_q = sfd_epd_rows[(size_t)r_o * M1 + m];
+        if (my_q >= 0) my_g = epd_gate[my_q];
+      }
+    }
+
+    for (int j = 0; j < n_dev; ++j) {
+      int r;
+      if (lists_fit) {
+        r = __builtin_amdgcn_readlane(my_row, j);
+      } else {
+        r = tok_sfd_row[(size_t)t * D + j];   // wave-uniform
+        if (r < 0) continue;
+      }
       float part[VPL][NE];
 #pragma unroll
       for (int i = 0; i < VPL; ++i)
@@ -89,9 +115,17 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
         for (int e = 0; e < NE; ++e) part[i][e] = 0.0f;
       // stage 1: gate-weighted sum of this device's expert outputs, slot order
       for (int m = 0; m < M1; ++m) {
-        const int q = sfd_epd_rows[(size_t)r * M1 + m];
-        if (q < 0) break;
-        const float g = epd_gate[q];
+        int q;
+        float g;
+        if (lists_fit) {
+          q = __builtin_amdgcn_readlane(my_q, j * M1 + m);
+          if (q < 0) break;
+          g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_g), j * M1 + m));
+        } else {
+          q = sfd_epd_rows[(size_t)r * M1 + m];
+          if (q < 0) break;
+          g = epd_gate[q];
+        }
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
           const int c = lane + 64 * i;
@@ -153,9 +187,10 @@ extern "C" int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((c.T + kCombWaves - 1) / kCombWaves), block(kCombWaves * 64);
   const int M1 = merge_width(c);
+  const int lists_fit = min_i(c.k, c.D) * M1 <= 64 ? 1 : 0;
 #define OCC_COMB(B, N)                                                                             \
   hipLaunchKernelGGL((combine_kernel<B, N>), grid, block, 0, s, epd_y, sfd_y, y_shared, y,         \
-                     plan->tok_sfd_row, plan->sfd_epd_rows, plan->epd_gate, c.T, c.D, M1, row_vecs)
+                     plan->tok_sfd_row, plan->sfd_epd_rows, plan->epd_gate, c.T, c.D, M1, row_vecs, lists_fit)
   if (c.dtype == OCCULT_BF16) {
     if (vpl <= 1) OCC_COMB(true, 1);
     else if (vpl <= 2) OCC_COMB(true, 2);
