@@ -27,8 +27,10 @@ __global__ __launch_bounds__(kDispWaves * 64) void dispatch_kernel(
       const int c = lane + 64 * i;
       if (c < row_vecs) v[i] = __builtin_nontemporal_load(src + c);
     }
+    // the token's D destination rows in one wave-wide load (D <= 64), then broadcast one by one
+    const int rl = lane < D ? tok_sfd_row[(size_t)t * D + lane] : -1;
     for (int j = 0; j < D; ++j) {
-      const int r = tok_sfd_row[(size_t)t * D + j];   // wave-uniform
+      const int r = __builtin_amdgcn_readlane(rl, j);
       if (r < 0) continue;
       u32x4* dst = sfd_x + (size_t)r * row_vecs;
 #pragma unroll
