@@ -4,11 +4,14 @@
 // The printed builders are sequential counters: BRIM_0 numbers (device, token) pairs
 // device-major / token-ascending, BRIM_1 numbers (local expert, SFD row) pairs expert-major /
 // row-ascending.  Both are stable ranks, so they are computed here without atomics:
-//   pass 1  plan_count : one token per thread; per block, how many of its 256 tokens touch each
-//                        device and each placement position (wave ballots + popcounts, LDS);
+//   pass 1  plan_count : one token per thread; per block of 256 tokens and device, how many of
+//                        the tokens touch the device and each of its placement positions (wave
+//                        ballots + popcounts, LDS);
 //   pass 2  plan_scan  : one block turns the [blocks][D+E] counts into exclusive bases
 //                        (column scan over blocks, then a scan over devices / positions);
-//   pass 3  plan_fill  : every block repeats its ballots and writes the rank-addressed tables.
+//   pass 3  plan_fill  : every block repeats its ballots and writes the rank-addressed tables;
+//                        one block per (256 tokens, device), so that D times more blocks share
+//                        the (device, slot) loop.
 // Inside a block the order is wave-major then lane = token-ascending, which is the order the
 // sequential counters would visit.  Every table is therefore bit-reproducible.
 #include "common.h"
@@ -51,19 +54,6 @@ __device__ __forceinline__ bool has_pos(const TokenBits& b, int P) {
   return (m >> (P & 63)) & 1ull;
 }
 
-// per-wave counts of the block's tokens per device and per position -> s_cnt[wave][col]
-__device__ __forceinline__ void wave_counts(const TokenBits& b, int D, int E, int wave, int lane,
-                                            int (*s_cnt)[kMaxCols]) {
-  for (int j = 0; j < D; ++j) {
-    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
-    if (lane == 0) s_cnt[wave][j] = __popcll(m);
-  }
-  for (int P = 0; P < E; ++P) {
-    const unsigned long long m = __ballot(has_pos(b, P));
-    if (lane == 0) s_cnt[wave][D + P] = __popcll(m);
-  }
-}
-
 __global__ __launch_bounds__(kTPB) void plan_count(const int32_t* __restrict__ ids, int T, int k, int E,
                                                    int D, int G, const int32_t* __restrict__ expert_pos,
                                                    uint64_t* __restrict__ tok_devmask,
@@ -75,11 +65,20 @@ __global__ __launch_bounds__(kTPB) void plan_count(const int32_t* __restrict__ i
   const int t = blockIdx.x * kTPB + threadIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
-  if (t < T) tok_devmask[t] = b.dev;
-  wave_counts(b, D, E, wave, lane, s_cnt);
+  const int j = blockIdx.y;   // this block counts device j and its G positions
+  if (j == 0 && t < T) tok_devmask[t] = b.dev;
+  {
+    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
+    if (lane == 0) s_cnt[wave][j] = __popcll(m);
+    for (int sl = 0; sl < G; ++sl) {
+      const unsigned long long mp = __ballot(has_pos(b, j * G + sl));
+      if (lane == 0) s_cnt[wave][D + j * G + sl] = __popcll(mp);
+    }
+  }
   __syncthreads();
   const int C = D + E;
-  for (int c = threadIdx.x; c < C; c += kTPB) {
+  for (int i = threadIdx.x; i <= G; i += kTPB) {
+    const int c = i == 0 ? j : D + j * G + i - 1;
     int sum = 0;
 #pragma unroll
     for (int wv = 0; wv < kWavesPerBlock; ++wv) sum += s_cnt[wv][c];
@@ -190,12 +189,22 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
     tpos[s] = live ? s_pos[ids[(size_t)t * k + s]] : -1;
     tgate[s] = live ? w[(size_t)t * k + s] : 0.0f;
   }
-  wave_counts(b, D, E, wave, lane, s_cnt);
+  // this block's device and its columns: the device itself and its G placement positions
+  const int j = blockIdx.y;
+  {
+    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
+    if (lane == 0) s_cnt[wave][j] = __popcll(m);
+    for (int sl = 0; sl < G; ++sl) {
+      const unsigned long long mp = __ballot(has_pos(b, j * G + sl));
+      if (lane == 0) s_cnt[wave][D + j * G + sl] = __popcll(mp);
+    }
+  }
   __syncthreads();
 
   // per-wave counts -> first rank of each wave in each column: block base + waves before it
   const int C = D + E;
-  for (int c = threadIdx.x; c < C; c += kTPB) {
+  for (int i = threadIdx.x; i <= G; i += kTPB) {
+    const int c = i == 0 ? j : D + j * G + i - 1;
     int run = blk_base[(size_t)blockIdx.x * C + c];
 #pragma unroll
     for (int wv = 0; wv < kWavesPerBlock; ++wv) {
@@ -208,7 +217,7 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
   const int* first = s_cnt[wave];
   const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 
-  for (int j = 0; j < D; ++j) {
+  {
     const bool on = (b.dev >> j) & 1ull;
     const unsigned long long m = __ballot(on);
     const int r = on ? first[j] + __popcll(m & lt) : -1;
@@ -263,7 +272,7 @@ extern "C" int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const fl
   const int nblk = (c.T + kTPB - 1) / kTPB;
   int32_t* blk = static_cast<int32_t*>(ws);
   if (nblk > 0) {
-    hipLaunchKernelGGL(plan_count, dim3(nblk), dim3(kTPB), 0, s, ids, c.T, c.k, c.E, c.D, G, c.expert_pos,
+    hipLaunchKernelGGL(plan_count, dim3(nblk, c.D), dim3(kTPB), 0, s, ids, c.T, c.k, c.E, c.D, G, c.expert_pos,
                        p.tok_devmask, blk);
     OCC_LAUNCH_CHECK("plan_count");
   }
@@ -274,7 +283,7 @@ extern "C" int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const fl
   OCC_LAUNCH_CHECK("plan_scan");
   if (nblk > 0) {
 #define OCC_PLAN_FILL(KM)                                                                              \
-  hipLaunchKernelGGL(plan_fill<KM>, dim3(nblk), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G,         \
+  hipLaunchKernelGGL(plan_fill<KM>, dim3(nblk, c.D), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G,    \
                      merge_width(c), c.expert_pos, blk, p.tok_sfd_row, p.sfd_token, p.epd_sfd_row,       \
                      p.epd_gate, p.sfd_epd_rows)
     if (c.k <= 8) OCC_PLAN_FILL(8);
