@@ -42,21 +42,53 @@ __device__ __forceinline__ float exp_ref(float z) {
   return z < -80.0f ? 0.0f : out;
 }
 
+// Cross-lane steps on the VALU's data-parallel primitives (no LDS crossbar): four symmetric
+// exchanges leave every lane of a 16-lane row with the row's result, two row broadcasts carry it
+// into lane 63, which is read back as a wave-uniform value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i(int own, int v) {
+  return __builtin_amdgcn_update_dpp(own, v, CTRL, ROW_MASK, 0xF, false);   // rows outside the mask keep `own`
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f(float own, float v) {
+  return __builtin_bit_cast(float, dpp_i<CTRL, ROW_MASK>(__builtin_bit_cast(int, own), __builtin_bit_cast(int, v)));
+}
+constexpr int kQuadSwap1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kQuadSwap2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141;
+constexpr int kRowMirror = 0x140;
+constexpr int kRowBcast15 = 0x142;     // lane 15 of each row into the next row (rows 1 and 3 take it)
+constexpr int kRowBcast31 = 0x143;     // lane 31 into rows 2 and 3
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void argmax_step(float& v, int& i) {
+  const float ov = dpp_f<CTRL, ROW_MASK>(v, v);
+  const int oi = dpp_i<CTRL, ROW_MASK>(i, i);
+  const bool take = (ov > v) || (ov == v && oi < i);
+  v = take ? ov : v;
+  i = take ? oi : i;
+}
+
+// larger value first, equal values -> lower index; result in every lane
 __device__ __forceinline__ void wave_argmax(float& v, int& i) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const float ov = __shfl_xor(v, off, 64);
-    const int oi = __shfl_xor(i, off, 64);
-    const bool take = (ov > v) || (ov == v && oi < i);
-    v = take ? ov : v;
-    i = take ? oi : i;
-  }
+  argmax_step<kQuadSwap1, 0xF>(v, i);
+  argmax_step<kQuadSwap2, 0xF>(v, i);
+  argmax_step<kRowHalfMirror, 0xF>(v, i);
+  argmax_step<kRowMirror, 0xF>(v, i);
+  argmax_step<kRowBcast15, 0xA>(v, i);
+  argmax_step<kRowBcast31, 0xC>(v, i);
+  v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+  i = __builtin_amdgcn_readlane(i, 63);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
+  v += dpp_f<kQuadSwap1, 0xF>(v, v);
+  v += dpp_f<kQuadSwap2, 0xF>(v, v);
+  v += dpp_f<kRowHalfMirror, 0xF>(v, v);
+  v += dpp_f<kRowMirror, 0xF>(v, v);
+  v += dpp_f<kRowBcast15, 0xA>(0.0f, v);
+  v += dpp_f<kRowBcast31, 0xC>(0.0f, v);
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 constexpr int kRouteWavesPerBlock = 4;
