@@ -91,6 +91,8 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching every call from the host "
                          "(measured: no faster on this runtime, 0.376 vs 0.363 ms on the decode workload)")
+    ap.add_argument("--no-standard", action="store_true",
+                    help="skip the comparison run with one simulated device per expert (standard dispatch)")
     ap.add_argument("--cpu-sample", type=int, default=16384)
     ap.add_argument("--call-reps", type=int, default=10)
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -247,6 +249,31 @@ def main():
                      "saved_fraction": 1.0 - st.bytes_occ / st.bytes_std,
                      "meta_bytes_per_token": st.bytes_meta / T},
     }
+    # The same layer with one simulated device per expert (D = E): the standard per-expert dispatch
+    # the paper compares against (a token's row is replicated once per selected expert, C_T = k).
+    if shape.E <= 64 and shape.n_d == 0 and not args.no_standard:
+        del layer
+        torch.cuda.empty_cache()
+        std = OccultLayer(T, d, f, shape.E, S, k, shape.E, shape.dtype, 0, 1, shape.renorm, None)
+        std.route(logits)
+        std.make_plan()
+        std.dispatch(x)
+        std.expert_ffn(x, wg, wu, wd)
+        sc = {
+            "plan": _event_time_ms(lambda: std.make_plan(), r),
+            "dispatch": _event_time_ms(lambda: std.dispatch(x), r),
+            "expert_ffn": _event_time_ms(lambda: std.expert_ffn(x, wg, wu, wd), r),
+            "combine": _event_time_ms(lambda: std.combine(), r),
+        }
+        sst = std.stats()
+        s3 = sc["dispatch"] + sc["expert_ffn"] + sc["combine"]
+        out["standard_per_expert_dispatch"] = {
+            "c_t": sst.c_t, "calls_ms": sc, "tokens_per_s_dispatch_ffn_combine": T / (s3 * 1e-3),
+            "bytes_per_token": sst.bytes_occ / T,
+            "occult_speedup_dispatch_ffn_combine": s3 / three,
+            "occult_speedup_dispatch_plus_combine": (sc["dispatch"] + sc["combine"]) / (calls["dispatch"] + calls["combine"]),
+        }
+        layer = std
     if not args.no_cpu_baseline:
         del layer
         out["cpu_baseline"] = cpu_baseline(wk, shape, args.cpu_sample)
