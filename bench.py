@@ -197,7 +197,16 @@ def main():
     tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12
     gbs = lambda by, ms: by / (ms * 1e-3) / 1e9
     bytes_router = (T * d + shape.E * d) * es + T * shape.E * 4 + T * k * 8
+    m1 = min(k, shape.E // shape.D)
+    bytes_route = T * (shape.E * 4 + k * 8)                       # scores in, ids and gates out
+    bytes_plan = (T * k * 8                                        # ids and gates in
+                  + T * 8 + T * shape.D * 4 + n_sfd * 4            # device masks, BRIM_0 rows, SFD -> token
+                  + 2 * n_epd * 4 + n_sfd * m1 * 4)                # EPD -> SFD row, gates, merge lists
     rooflines = {
+        "route": {"bound": "hbm", "achieved": gbs(bytes_route, calls["route"]), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                  "note": "launch- and latency-bound at this size"},
+        "plan": {"bound": "hbm", "achieved": gbs(bytes_plan, calls["plan"]), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                 "note": "three dependent launches; latency-bound"},
         "router_projection_and_route": {"bound": "hbm", "achieved": gbs(bytes_router, calls["router_projection_and_route"]),
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s"},
         "ffn_gemm1_swiglu": {"bound": "mfma", "achieved": tf(flops1, calls["ffn_gemm1_swiglu"]),
