@@ -199,3 +199,27 @@ def test_shared_down_projection_split_over_k_matches_unsplit():
         say(f"  shared experts: max-abs {mx:.3e} mean-abs {mean:.3e}")
         assert mx <= 2e-2 and mean <= 2e-3
     assert np.max(np.abs(outs[0] - outs[1])) <= 2e-2
+
+
+def test_empty_batch_runs_every_call():
+    """T = 0: every entry point returns without touching memory (the Gram matrix is still cleared)."""
+    from paper_2505_13345_amd import binding as B
+    dev = require_gpu()
+    E, D, k, d, f, S = 16, 4, 4, 128, 64, 1
+    layer = OccultLayer(0, d, f, E, S, k, D, "bf16")
+    x = torch.zeros((0, d), dtype=torch.bfloat16, device=dev)
+    wg = torch.zeros((E + S, f, d), dtype=torch.bfloat16, device=dev)
+    wd = torch.zeros((E + S, d, f), dtype=torch.bfloat16, device=dev)
+    y = layer.forward(torch.zeros((0, E), device=dev), x, wg, wg, wd)
+    assert y.shape == (0, d)
+    wr = torch.zeros((E, d), dtype=torch.bfloat16, device=dev)
+    layer.route_from_hidden(x, wr, torch.zeros((0, E), device=dev))
+    B.occult_dispatch_meta(layer.cfg, layer.plan, layer.ids, layer.w,
+                           torch.zeros((1, k), dtype=torch.int32, device=dev), torch.zeros((1, k), device=dev))
+    gram = torch.full((E, E), 5.0, dtype=torch.float64, device=dev)
+    B.occult_similarity_gram(layer.cfg, torch.zeros((0, E), device=dev), gram, accumulate=False)
+    C = torch.full((E, E), 5, dtype=torch.int32, device=dev)
+    B.occult_coactivation(layer.cfg, layer.ids, C, False)
+    torch.cuda.synchronize()
+    assert float(gram.abs().max()) == 0.0 and int(C.abs().max()) == 0
+    assert layer.stats().n_sfd == 0
