@@ -976,8 +976,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_bf16(const float* __restric
 
 // K slices for a product whose tiles alone would leave most of the chip idle (0 = do not split)
 static int choose_ksplit(long long tiles, int nk) {
-  if (tiles >= 128 || nk < 8) return 0;
-  long long ks = 256 / tiles;
+  if (tiles >= 384 || nk < 8) return 0;   // beyond that the 256-row tiles fill the chip by themselves
+  long long ks = 1024 / tiles;   // about two rounds of 512 resident workgroups
   if (ks > nk / 4) ks = nk / 4;
   if (ks > 8) ks = 8;
   return ks >= 2 ? (int)ks : 0;
@@ -989,7 +989,7 @@ static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, in
     const int groups = a.ngroups;
     // 256-row tiles once groups average >= 192 rows, every A byte offset fits 32 bits and there
     // are at least two K tiles to pipeline
-    const bool use_big = (long long)total_rows >= 192ll * groups &&
+    const bool use_big = (long long)total_rows >= 192ll * groups && a.ksplit <= 1 &&
                          (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK;
     // groups averaging under 24 rows: weight streaming, one wave per 32 columns x 32 tokens
     const bool use_skinny = !use_big && (long long)total_rows < 24ll * groups && a.N % skinny::BN_OUT == 0;
@@ -1062,7 +1062,7 @@ using namespace occult;
 static size_t ffn_ws_need(const occult_cfg_t& c, int* ksplit_out) {
   *ksplit_out = 0;
   if (c.S == 0 || c.dtype != OCCULT_BF16 || c.T == 0) return 0;
-  if (c.T >= 192 || c.T < 24) return 0;   // those batches take the 256-row tiles / the weight-streaming kernel
+  if (c.T < 24) return 0;   // those batches take the weight-streaming kernel
   const long long tiles = (long long)((c.T + 127) / 128) * ((c.d + 127) / 128);
   const int ks = choose_ksplit(tiles, c.S * c.f / 64);
   if (ks == 0 || c.d % 4 != 0) return 0;
