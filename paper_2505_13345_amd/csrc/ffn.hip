@@ -987,9 +987,13 @@ static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, in
   if (total_rows == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
     const int groups = a.ngroups;
-    // 256-row tiles once groups average >= 192 rows, every A byte offset fits 32 bits and there
+    // 256-row tiles once groups average enough rows, every A byte offset fits 32 bits and there
     // are at least two K tiles to pipeline
-    const bool use_big = (long long)total_rows >= 192ll * groups && a.ksplit <= 1 &&
+    // (measured on 60 experts, d = 2048, f = 1408: the gate/up product is weight-bound on the
+    // 128-row tiles until an expert's rows no longer fit one of them; the down projection is
+    // faster on the 256-row tiles from about 64 rows per expert)
+    const long long big_rows = a.grp_offset == nullptr ? 192 : (swiglu ? 129 : 64);
+    const bool use_big = (long long)total_rows >= big_rows * groups && a.ksplit <= 1 &&
                          (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK;
     // groups averaging under 24 rows: weight streaming, one wave per 32 columns x 32 tokens
     const bool use_skinny = !use_big && (long long)total_rows < 24ll * groups && a.N % skinny::BN_OUT == 0;
