@@ -31,11 +31,11 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 
 # HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs scaled by a copy kernel of known size (profiles/<workload>_hbm_traffic.txt:
-# FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0).  prefill: the gate/up GEMM; decode: the four
+# FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0).  prefill: the gate/up GEMM; decode: the five
 # kernels of occult_expert_ffn together (its roofline is on all weight bytes).  Absent = not measured.
 MEASURED_TRAFFIC = {
-    "prefill_bf16": (1063011 * 2.0 + 262144) * 1024,
-    "decode_bf16": ((355416 + 190314 + 23617 + 11998) * 2.0 + (1426 + 2049 + 1408 + 512)) * 1024,
+    "prefill_bf16": (1060460 * 2.0 + 262144) * 1024,
+    "decode_bf16": ((355433 + 190349 + 24685 + 17042 + 4113) * 2.0 + (1427 + 2049 + 1408 + 8192 + 512)) * 1024,
 }
 
 
