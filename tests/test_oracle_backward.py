@@ -1,0 +1,194 @@
+"""Pins for oracle/backward.py.  None of them retypes its loops: gradients are checked against
+finite differences of the pinned forward oracles (exact for the linear and bilinear maps),
+against closed forms of special cases, and against invariants."""
+import numpy as np
+import pytest
+
+from inputs import workloads as wl
+from oracle import backward, moe_std, occult_ref, routing
+
+
+def _instance(seed, T, E, k, D, d, clustered=True):
+    rng = np.random.default_rng(seed)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    pos = rng.permutation(E).astype(np.int32) if clustered else np.arange(E, dtype=np.int32)
+    ids, w = routing.route(logits, k, D, pos)
+    x = rng.standard_normal((T, d))
+    g_y = rng.standard_normal((T, d))
+    return logits, pos, ids, w, x, g_y
+
+
+def _layer_backward_bypass(x, ids, w, pos, D, scale, g_y):
+    """Gradient of <g_y, y> for the forward oracle's identity experts E_e(v) = scale[e] * v:
+    an expert's output rows are scale * its input rows, and its backward scales the gradient."""
+    tr = occult_ref.moe_forward(x, ids, w, pos, D, bypass_scale=scale)
+    L = occult_ref.placement_lists(pos, D)
+    offs = np.concatenate([[0], np.cumsum(tr.dev_count)])
+    out_epd = []
+    for j in range(D):
+        seg = tr.x_sfd[int(offs[j]):int(offs[j + 1])]
+        rows = np.zeros((int((tr.brim_1[j] >= 0).sum()), x.shape[1]))
+        for e in range(len(L[j])):
+            v = tr.brim_1[j][e]
+            rows[v[v >= 0]] = scale[L[j][e]] * seg[v >= 0]
+        out_epd.append(rows)
+    g_sfd, g_out, g_w = backward.combine_backward(g_y, out_epd, tr.brim_0, tr.brim_1, tr.brim_w, tr.dev_count)
+    g_in = []
+    for j in range(D):
+        rows = g_out[j].copy()
+        for e in range(len(L[j])):
+            v = tr.brim_1[j][e]
+            rows[v[v >= 0]] *= scale[L[j][e]]
+        g_in.append(rows)
+    g_sfd_x, g_x = backward.dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count)
+    g_slots = backward.gate_grad_to_slots(g_w, ids, tr.brim_0, L, tr.dev_count)
+    return tr, g_sfd, g_x, g_slots
+
+
+@pytest.mark.parametrize("T,E,k,D", [(13, 8, 3, 4), (9, 12, 4, 3), (7, 6, 6, 2), (11, 8, 2, 8), (5, 4, 1, 2)])
+def test_layer_gradient_matches_finite_differences_of_forward_oracle(T, E, k, D):
+    d = 5
+    logits, pos, ids, w, x, g_y = _instance(T * 31 + E, T, E, k, D, d)
+    scale = np.linspace(0.5, 2.0, E)
+    tr, g_sfd, g_x, g_slots = _layer_backward_bypass(x, ids, w, pos, D, scale, g_y)
+
+    def loss(xx, ww):
+        return float(np.sum(g_y * occult_ref.moe_forward(xx, ids, ww, pos, D, bypass_scale=scale).y))
+
+    # the layer is linear in x and in w separately: central differences are exact up to rounding
+    for t in range(T):
+        for c in range(d):
+            e = np.zeros_like(x)
+            e[t, c] = 1.0
+            assert g_x[t, c] == pytest.approx((loss(x + e, w) - loss(x - e, w)) / 2, rel=1e-10, abs=1e-10)
+    for t in range(T):
+        for s in range(k):
+            e = np.zeros_like(w)
+            e[t, s] = 1.0
+            assert g_slots[t, s] == pytest.approx((loss(x, w + e) - loss(x, w - e)) / 2, rel=1e-10, abs=1e-10)
+    # transposed combine = dispatch of the output gradient: every SFD row holds its token's gradient
+    g_sfd_chk, _, _ = occult_ref.dispatch(g_y, ids, w, tr.brim_0)
+    assert np.array_equal(g_sfd, g_sfd_chk)
+
+
+def test_gate_gradient_with_swiglu_experts_is_directional_derivative_of_forward_oracle():
+    T, E, k, D, d, f = 10, 8, 3, 4, 6, 7
+    logits, pos, ids, w, x, g_y = _instance(5, T, E, k, D, d)
+    rng = np.random.default_rng(9)
+    wg = rng.standard_normal((E, f, d)) / 2
+    wu = rng.standard_normal((E, f, d)) / 2
+    wd = rng.standard_normal((E, d, f)) / 2
+    tr = occult_ref.moe_forward(x, ids, w, pos, D, wg, wu, wd)
+    L = occult_ref.placement_lists(pos, D)
+    offs = np.concatenate([[0], np.cumsum(tr.dev_count)])
+    out_epd = []
+    for j in range(D):
+        seg = tr.x_sfd[int(offs[j]):int(offs[j + 1])]
+        rows = np.zeros((int((tr.brim_1[j] >= 0).sum()), d))
+        for e in range(len(L[j])):
+            v = tr.brim_1[j][e]
+            rows[v[v >= 0]] = moe_std.expert_ffn(seg[v >= 0], wg[L[j][e]], wu[L[j][e]], wd[L[j][e]], np.float64)
+        out_epd.append(rows)
+    _, _, g_w = backward.combine_backward(g_y, out_epd, tr.brim_0, tr.brim_1, tr.brim_w, tr.dev_count)
+    g_slots = backward.gate_grad_to_slots(g_w, ids, tr.brim_0, L, tr.dev_count)
+    v = rng.standard_normal(w.shape)
+
+    def loss(ww):
+        return float(np.sum(g_y * occult_ref.moe_forward(x, ids, ww, pos, D, wg, wu, wd).y))
+
+    assert np.sum(g_slots * v) == pytest.approx((loss(w + v) - loss(w - v)) / 2, rel=1e-10)
+    # and against the plain (not deduplicated) layer
+    def loss_std(ww):
+        return float(np.sum(g_y * moe_std.moe_layer(x, ids, ww, wg, wu, wd, E)))
+
+    assert np.sum(g_slots * v) == pytest.approx((loss_std(w + v) - loss_std(w - v)) / 2, rel=1e-10)
+
+
+def test_dispatch_backward_special_cases():
+    # k = 1: one EPD row per token, the backward is the inverse permutation of the forward gather
+    T, E, D, d = 12, 6, 3, 4
+    logits, pos, ids, w, x, _ = _instance(3, T, E, 1, D, d)
+    tr = occult_ref.moe_forward(x, ids, w, pos, D)
+    L = occult_ref.placement_lists(pos, D)
+    offs = np.concatenate([[0], np.cumsum(tr.dev_count)])
+    g_in, token_of = [], []
+    for j in range(D):
+        n = int((tr.brim_1[j] >= 0).sum())
+        toks = np.zeros(n, dtype=np.int64)
+        for e in range(len(L[j])):
+            v = tr.brim_1[j][e]
+            sfd_rows = np.nonzero(v >= 0)[0] + int(offs[j])
+            for r, q in zip(sfd_rows, v[v >= 0]):
+                toks[q] = int(np.nonzero(tr.brim_0[j] == r)[0][0])
+        token_of.append(toks)
+        g_in.append(np.arange(n * d, dtype=np.float64).reshape(n, d) + 100 * j)
+    _, g_x = backward.dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count)
+    for j in range(D):
+        assert np.array_equal(g_x[token_of[j]], g_in[j])
+    # every expert its own device (classical dispatch): g_x[t] = sum over the token's k rows, exactly
+    T, E, k = 9, 6, 3
+    logits, pos, ids, w, x, _ = _instance(4, T, E, k, E, d, clustered=False)
+    tr = occult_ref.moe_forward(x, ids, w, pos, E)
+    g_in = [np.full((int(tr.dev_count[j]), d), float(2 ** j)) for j in range(E)]   # device j = expert j
+    g_sfd, g_x = backward.dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count)
+    want = np.array([[sum(2.0 ** int(e) for e in ids[t])] * d for t in range(T)])
+    assert np.array_equal(g_x, want)
+    assert g_sfd.shape[0] == T * k
+    # the payload rounding hook is applied to the SFD rows before the second stage
+    g_sfd_r, g_x_r = backward.dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count, sfd_round=lambda a: a * 0)
+    assert not g_sfd_r.any() and not g_x_r.any()
+
+
+def test_route_backward_closed_forms():
+    rng = np.random.default_rng(0)
+    T, E = 6, 8
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    p = routing.softmax64(logits)
+    # all experts selected, no renormalisation: the softmax Jacobian, w in slot order
+    ids = np.array([rng.permutation(E) for _ in range(T)], dtype=np.int32)
+    g_w = rng.standard_normal((T, E))
+    g_p = np.zeros((T, E))
+    for t in range(T):
+        g_p[t, ids[t]] = g_w[t]
+    want = np.stack([(np.diag(p[t]) - np.outer(p[t], p[t])) @ g_p[t] for t in range(T)])
+    assert np.allclose(backward.route_backward(logits, ids, g_w, renorm=0), want, rtol=1e-12, atol=1e-15)
+    # all experts selected and renormalised: Z = 1, same gradient
+    assert np.allclose(backward.route_backward(logits, ids, g_w, renorm=1), want, rtol=1e-10, atol=1e-14)
+    # k < E renormalised: the gates are a softmax over the selected scores alone
+    k = 3
+    ids = np.array([rng.permutation(E)[:k] for _ in range(T)], dtype=np.int32)
+    g_w = rng.standard_normal((T, k))
+    got = backward.route_backward(logits, ids, g_w, renorm=1)
+    want = np.zeros((T, E))
+    for t in range(T):
+        l = logits[t, ids[t]].astype(np.float64)
+        q = np.exp(l - l.max())
+        q /= q.sum()
+        want[t, ids[t]] = (np.diag(q) - np.outer(q, q)) @ g_w[t]
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-14)
+    # shift invariance of the softmax: every row of the gradient sums to zero
+    ids = np.array([rng.permutation(E)[:k] for _ in range(T)], dtype=np.int32)
+    for renorm in (0, 1):
+        assert np.allclose(backward.route_backward(logits, ids, g_w, renorm).sum(axis=1), 0, atol=1e-14)
+
+
+@pytest.mark.parametrize("renorm", [0, 1])
+def test_route_backward_is_derivative_of_the_routing_oracle(renorm):
+    rng = np.random.default_rng(2)
+    T, E, k, D = 8, 12, 4, 3
+    # scores on a grid of 1/64 so that +-h is exact in float32; distinct, so the selection holds
+    logits = (rng.permutation(T * E).reshape(T, E) / 64.0).astype(np.float32)
+    ids, _ = routing.route(logits, k, D, renorm=renorm)
+    g_w = rng.standard_normal((T, k))
+    g = backward.route_backward(logits, ids, g_w, renorm)
+    h = np.float32(2.0 ** -9)
+    for t in range(T):
+        for e in range(E):
+            lp, lm = logits.copy(), logits.copy()
+            lp[t, e] += h
+            lm[t, e] -= h
+            ids_p, w_p = routing.route(lp, k, D, renorm=renorm)
+            ids_m, w_m = routing.route(lm, k, D, renorm=renorm)
+            assert np.array_equal(ids_p, ids) and np.array_equal(ids_m, ids)
+            fd = np.sum(g_w * (w_p - w_m)) / (2 * float(h))
+            assert g[t, e] == pytest.approx(fd, rel=2e-4, abs=1e-7)
