@@ -93,6 +93,8 @@ def main():
                          "(measured: no faster on this runtime, 0.376 vs 0.363 ms on the decode workload)")
     ap.add_argument("--no-standard", action="store_true",
                     help="skip the comparison run with one simulated device per expert (standard dispatch)")
+    ap.add_argument("--no-backward", action="store_true",
+                    help="skip timing the backward calls of the data movement (occult_combine_backward, ...)")
     ap.add_argument("--cpu-sample", type=int, default=16384)
     ap.add_argument("--call-reps", type=int, default=10)
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -237,6 +239,35 @@ def main():
         dom["kernel"] = "t256::grouped_gemm_bf16<SWIGLU> (gate/up projections of occult_expert_ffn)"
     dom["traffic"] = MEASURED_TRAFFIC.get(args.workload)
 
+    # backward pass of the data movement and of the routing weights (not part of the step: reported beside it)
+    backward = None
+    if not args.no_backward:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        dy = torch.randn((T, d), device=dev, generator=gen).to(tdt)
+        dlogits = torch.empty_like(logits)
+        layer.combine_backward(dy)
+        bc = {
+            "combine_backward": _event_time_ms(lambda: layer.combine_backward(dy), r),
+            "combine_backward_rows_only": _event_time_ms(lambda: layer.combine_backward(dy, want_dw=False), r),
+            "dispatch_backward": _event_time_ms(lambda: layer.dispatch_backward(layer.epd_dy), r),
+            "route_backward": _event_time_ms(lambda: layer.route_backward(logits, layer.dw, dlogits), r),
+        }
+        bb = {
+            # dispatch of dy (T rows in, N_sfd out) + scaled rows (T in, N_epd out) + gate gradients (N_epd in)
+            "combine_backward": (2 * T + n_sfd + 2 * n_epd) * row,
+            "combine_backward_rows_only": (2 * T + n_sfd + n_epd) * row,
+            "dispatch_backward": (n_epd + n_sfd + T) * row,
+            "route_backward": T * (2 * shape.E * 4 + k * 8),
+        }
+        backward = {"calls_ms": bc,
+                    "rooflines": {n: {"bound": "hbm", "achieved": gbs(bb[n], bc[n]), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                      "frac": gbs(bb[n], bc[n]) / PEAK_HBM_GBS} for n in bc}}
+        for n in ("sfd_dy", "epd_dy", "sfd_dx", "dx", "dw"):
+            setattr(layer, n, None)
+        del dy, dlogits
+        torch.cuda.empty_cache()
+
     three = calls["dispatch"] + calls["expert_ffn"] + calls["combine"]
     out = {
         "metric": "MoE-layer tokens/sec (dispatch+FFN+combine)",
@@ -258,6 +289,8 @@ def main():
                      "saved_fraction": 1.0 - st.bytes_occ / st.bytes_std,
                      "meta_bytes_per_token": st.bytes_meta / T},
     }
+    if backward is not None:
+        out["backward_data_movement"] = backward
     # The same layer with one simulated device per expert (D = E): the standard per-expert dispatch
     # the paper compares against (a token's row is replicated once per selected expert, C_T = k).
     if shape.E <= 64 and shape.n_d == 0 and not args.no_standard:

@@ -1,7 +1,7 @@
 /*
- * occult.h - C ABI of the MI355X (gfx950) library for the forward hot path of a
- * collaboration-aware expert-parallel mixture-of-experts layer
- * (Occult, arXiv 2505.13345).
+ * occult.h - C ABI of the MI355X (gfx950) library for the hot path of a collaboration-aware
+ * expert-parallel mixture-of-experts layer (Occult, arXiv 2505.13345): the forward pass, and the
+ * backward pass of its data movement and routing weights.
  *
  * One GPU's share of the layer: the D devices of expert parallelism are simulated as
  * groups of G = E / D experts on one GPU, the rows they would exchange are packed into
@@ -225,6 +225,39 @@ int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, con
  * epd_y [N_epd][d], sfd_y [>= N_sfd][d], y [T][d]; device ptrs.  Order-fixed, no atomics. */
 int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_y,
                    void* sfd_y, const void* y_shared, void* y, occult_stream_t stream);
+
+/* Backward pass of the data movement (the paper trains through the layer: Introduction, Sec. 4
+ * Training; it prints no backward algorithm, and every forward step here is linear in the hidden
+ * rows, so the gradient is the transposed map on the same plan, Sec. 3.1).  Both calls leave the
+ * plan untouched and are order-fixed like the forward calls.
+ *
+ * occult_combine_backward: given dy [T][d] (gradient of occult_combine's y),
+ *   sfd_dy[r] = dy[token of SFD row r]                     [>= N_sfd][d]  (transposed stage 2: the
+ *               payload of the first backward exchange; exactly occult_dispatch of dy)
+ *   epd_dy[q] = epd_gate[q] * dy[token of EPD row q]       [N_epd][d]     rounded to cfg.dtype
+ *   dw[t][s]  = < dy[t], epd_y[EPD row of (t, ids[t][s])] >  [T][k] f32    (f32 accumulation)
+ * sfd_dy, epd_dy and dw are each optional (NULL = not produced); dw needs epd_y, the expert
+ * outputs of the forward pass; ids [T][k] is the routing the plan was built from.  The gradient of
+ * y_shared is dy itself.
+ *
+ * occult_dispatch_backward: given epd_dx [N_epd][d] (gradient of every expert's input row, i.e. of
+ * sfd_x[epd_sfd_row[q]] as read by the first product),
+ *   sfd_dx[r] = sum over the EPD rows q of SFD row r, slot order, of epd_dx[q]   [>= N_sfd][d]
+ *               (f32 accumulation, stored in cfg.dtype: the payload of the backward return trip)
+ *   dx[t]     = sum over devices j ascending of sfd_dx[tok_sfd_row[t][j]] (+ dx_shared[t] if not NULL)
+ * i.e. the two-stage sum of occult_combine with unit weights. */
+int occult_combine_backward(const occult_cfg_t* cfg, const occult_plan_t* plan, const int32_t* ids,
+                            const void* dy, const void* epd_y, void* sfd_dy, void* epd_dy, float* dw,
+                            occult_stream_t stream);
+int occult_dispatch_backward(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_dx,
+                             void* sfd_dx, const void* dx_shared, void* dx, occult_stream_t stream);
+
+/* Gradient of the routing weights with respect to the router scores (paper Eq. 1: Softmax over
+ * all E experts, the values at the selected experts, divided by their sum if cfg.renorm; the
+ * selection is piecewise constant and has no gradient).  logits [T][E] f32, ids [T][k] as returned
+ * by occult_route, dw [T][k] f32 -> dlogits [T][E] f32, all device ptrs; f32 arithmetic. */
+int occult_route_backward(const occult_cfg_t* cfg, const float* logits, const int32_t* ids, const float* dw,
+                          float* dlogits, occult_stream_t stream);
 
 /* Co-activation counts (paper Preliminary, co-activation graph): C[i][j] = number of tokens
  * whose selected experts include both i and j (diagonal = expert load).  ids [T][k], C [E][E]

@@ -23,6 +23,7 @@ EXPORTS = [
     "occult_plan", "occult_dispatch", "occult_expert_ffn", "occult_combine", "occult_coactivation",
     "occult_placement_greedy", "occult_plan_stats", "occult_router", "occult_dispatch_meta",
     "occult_similarity_gram", "occult_similarity_table", "occult_expert_ffn_ws_bytes", "occult_expert_ffn_ws",
+    "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
 ]
 
 
@@ -89,6 +90,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_expert_ffn_ws.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t),
                                          c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.occult_combine.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.occult_combine_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                            c_void_p]
+    lib.occult_dispatch_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.occult_route_backward.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_coactivation.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_placement_greedy.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
     lib.occult_plan_stats.argtypes = [cfgp, planp, POINTER(occult_stats_t), c_void_p]
@@ -212,6 +217,21 @@ def occult_expert_ffn_ws(cfg, plan, sfd_x, x, w_gate, w_up, w_down, epd_h, epd_y
 def occult_combine(cfg, plan, epd_y, sfd_y, y_shared, y, stream=None) -> None:
     _check(load_library().occult_combine(ctypes.byref(cfg), ctypes.byref(plan), _ptr(epd_y), _ptr(sfd_y),
                                          _ptr(y_shared), _ptr(y), _stream(stream)))
+
+
+def occult_combine_backward(cfg, plan, ids, dy, epd_y, sfd_dy, epd_dy, dw, stream=None) -> None:
+    _check(load_library().occult_combine_backward(ctypes.byref(cfg), ctypes.byref(plan), _ptr(ids), _ptr(dy),
+                                                  _ptr(epd_y), _ptr(sfd_dy), _ptr(epd_dy), _ptr(dw), _stream(stream)))
+
+
+def occult_dispatch_backward(cfg, plan, epd_dx, sfd_dx, dx_shared, dx, stream=None) -> None:
+    _check(load_library().occult_dispatch_backward(ctypes.byref(cfg), ctypes.byref(plan), _ptr(epd_dx), _ptr(sfd_dx),
+                                                   _ptr(dx_shared), _ptr(dx), _stream(stream)))
+
+
+def occult_route_backward(cfg, logits, ids, dw, dlogits, stream=None) -> None:
+    _check(load_library().occult_route_backward(ctypes.byref(cfg), _ptr(logits), _ptr(ids), _ptr(dw), _ptr(dlogits),
+                                                _stream(stream)))
 
 
 def occult_coactivation(cfg, ids, C, accumulate: bool = False, stream=None) -> None:

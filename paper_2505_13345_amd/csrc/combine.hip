@@ -11,55 +11,14 @@
 // added to the token's accumulator from registers, so sfd_y is written once and not read again.
 // Traffic per token: k EPD rows in, c_t SFD rows out, one ORI row out (+ one shared row in).
 // The arithmetic (orders, roundings) is that of the two separate stages; no atomics.
+//
+// With unit weights the same kernel is the backward of dispatch and of the first product's row
+// gather (occult_dispatch_backward): both are sums of replicas back into the row they came from.
 #include "common.h"
 
 namespace occult {
 
 constexpr int kCombWaves = 4;
-
-template <bool BF16>
-struct Row;
-
-// bf16: a 16-byte vector = 8 elements
-template <>
-struct Row<true> {
-  static constexpr int kElems = 8;
-  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
-    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(base) + row * row_vecs + c);
-    out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x);
-    out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
-    out[4] = bf16_lo(v.z); out[5] = bf16_hi(v.z);
-    out[6] = bf16_lo(v.w); out[7] = bf16_hi(v.w);
-  }
-  // stores the rounded values and returns them in `vals`
-  __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
-    u32x4 v;
-    v.x = pack_bf16(vals[0], vals[1]);
-    v.y = pack_bf16(vals[2], vals[3]);
-    v.z = pack_bf16(vals[4], vals[5]);
-    v.w = pack_bf16(vals[6], vals[7]);
-    __builtin_nontemporal_store(v, static_cast<u32x4*>(base) + row * row_vecs + c);
-    vals[0] = bf16_lo(v.x); vals[1] = bf16_hi(v.x);
-    vals[2] = bf16_lo(v.y); vals[3] = bf16_hi(v.y);
-    vals[4] = bf16_lo(v.z); vals[5] = bf16_hi(v.z);
-    vals[6] = bf16_lo(v.w); vals[7] = bf16_hi(v.w);
-  }
-};
-
-// f32: a 16-byte vector = 4 elements
-template <>
-struct Row<false> {
-  static constexpr int kElems = 4;
-  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
-    const f32x4 v = __builtin_nontemporal_load(static_cast<const f32x4*>(base) + row * row_vecs + c);
-    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
-  }
-  __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
-    f32x4 v;
-    v.x = vals[0]; v.y = vals[1]; v.z = vals[2]; v.w = vals[3];
-    __builtin_nontemporal_store(v, static_cast<f32x4*>(base) + row * row_vecs + c);
-  }
-};
 
 template <bool BF16, int VPL>
 __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
@@ -96,7 +55,7 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
       const int r_o = __shfl(my_row, o < 64 ? o : 0, 64);
       if (o < n_dev) {
         my_q = sfd_epd_rows[(size_t)r_o * M1 + m];
-        if (my_q >= 0) my_g = epd_gate[my_q];
+        if (my_q >= 0) my_g = epd_gate ? epd_gate[my_q] : 1.0f;
       }
     }
 
@@ -124,7 +83,7 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
         } else {
           q = sfd_epd_rows[(size_t)r * M1 + m];
           if (q < 0) break;
-          g = epd_gate[q];
+          g = epd_gate ? epd_gate[q] : 1.0f;
         }
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
@@ -164,22 +123,12 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
   }
 }
 
-}  // namespace occult
-
-using namespace occult;
-
-extern "C" int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_y,
-                              void* sfd_y, const void* y_shared, void* y, occult_stream_t stream) {
-  int rc = check_cfg(cfg);
-  if (rc) return rc;
-  const occult_cfg_t c = *cfg;
-  if (c.T == 0) return OCCULT_OK;
-  OCC_REQUIRE(plan && plan->tok_sfd_row && plan->sfd_epd_rows && plan->epd_gate, OCCULT_ENULLPTR,
-              "plan or one of its tables is NULL");
-  OCC_REQUIRE(epd_y && sfd_y && y, OCCULT_ENULLPTR, "epd_y, sfd_y or y is NULL");
+// launches the two-stage sum; gates == NULL means unit weights
+static int launch_combine(const occult_cfg_t& c, const occult_plan_t* plan, const float* gates, const void* epd,
+                          void* sfd, const void* shared, void* out, occult_stream_t stream) {
   const size_t row_bytes = (size_t)c.d * elem_size(c);
   OCC_REQUIRE(row_bytes % 16 == 0, OCCULT_EALIGN, "row of %zu bytes is not a multiple of 16", row_bytes);
-  OCC_REQUIRE(aligned16(epd_y) && aligned16(sfd_y) && aligned16(y) && aligned16(y_shared), OCCULT_EALIGN,
+  OCC_REQUIRE(aligned16(epd) && aligned16(sfd) && aligned16(out) && aligned16(shared), OCCULT_EALIGN,
               "a buffer is not 16-byte aligned");
   const int row_vecs = (int)(row_bytes / 16);
   const int vpl = (row_vecs + 63) / 64;
@@ -189,8 +138,8 @@ extern "C" int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan
   const int M1 = merge_width(c);
   const int lists_fit = min_i(c.k, c.D) * M1 <= 64 ? 1 : 0;
 #define OCC_COMB(B, N)                                                                             \
-  hipLaunchKernelGGL((combine_kernel<B, N>), grid, block, 0, s, epd_y, sfd_y, y_shared, y,         \
-                     plan->tok_sfd_row, plan->sfd_epd_rows, plan->epd_gate, c.T, c.D, M1, row_vecs, lists_fit)
+  hipLaunchKernelGGL((combine_kernel<B, N>), grid, block, 0, s, epd, sfd, shared, out,             \
+                     plan->tok_sfd_row, plan->sfd_epd_rows, gates, c.T, c.D, M1, row_vecs, lists_fit)
   if (c.dtype == OCCULT_BF16) {
     if (vpl <= 1) OCC_COMB(true, 1);
     else if (vpl <= 2) OCC_COMB(true, 2);
@@ -205,4 +154,32 @@ extern "C" int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan
 #undef OCC_COMB
   OCC_LAUNCH_CHECK("combine_kernel");
   return OCCULT_OK;
+}
+
+}  // namespace occult
+
+using namespace occult;
+
+extern "C" int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_y,
+                              void* sfd_y, const void* y_shared, void* y, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  if (c.T == 0) return OCCULT_OK;
+  OCC_REQUIRE(plan && plan->tok_sfd_row && plan->sfd_epd_rows && plan->epd_gate, OCCULT_ENULLPTR,
+              "plan or one of its tables is NULL");
+  OCC_REQUIRE(epd_y && sfd_y && y, OCCULT_ENULLPTR, "epd_y, sfd_y or y is NULL");
+  return launch_combine(c, plan, plan->epd_gate, epd_y, sfd_y, y_shared, y, stream);
+}
+
+// Transpose of the SFD -> EPD row gather and of dispatch: the same two-stage sum with unit weights.
+extern "C" int occult_dispatch_backward(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_dx,
+                                        void* sfd_dx, const void* dx_shared, void* dx, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  if (c.T == 0) return OCCULT_OK;
+  OCC_REQUIRE(plan && plan->tok_sfd_row && plan->sfd_epd_rows, OCCULT_ENULLPTR, "plan or one of its tables is NULL");
+  OCC_REQUIRE(epd_dx && sfd_dx && dx, OCCULT_ENULLPTR, "epd_dx, sfd_dx or dx is NULL");
+  return launch_combine(c, plan, nullptr, epd_dx, sfd_dx, dx_shared, dx, stream);
 }

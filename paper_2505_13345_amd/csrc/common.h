@@ -64,6 +64,51 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));   // one packed conversion
 }
 
+// One 16-byte vector of a hidden row as floats: load, and store with the rounding of the storage type.
+template <bool BF16>
+struct Row;
+
+// bf16: a 16-byte vector = 8 elements
+template <>
+struct Row<true> {
+  static constexpr int kElems = 8;
+  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
+    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(base) + row * row_vecs + c);
+    out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x);
+    out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
+    out[4] = bf16_lo(v.z); out[5] = bf16_hi(v.z);
+    out[6] = bf16_lo(v.w); out[7] = bf16_hi(v.w);
+  }
+  // stores the rounded values and returns them in `vals`
+  __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
+    u32x4 v;
+    v.x = pack_bf16(vals[0], vals[1]);
+    v.y = pack_bf16(vals[2], vals[3]);
+    v.z = pack_bf16(vals[4], vals[5]);
+    v.w = pack_bf16(vals[6], vals[7]);
+    __builtin_nontemporal_store(v, static_cast<u32x4*>(base) + row * row_vecs + c);
+    vals[0] = bf16_lo(v.x); vals[1] = bf16_hi(v.x);
+    vals[2] = bf16_lo(v.y); vals[3] = bf16_hi(v.y);
+    vals[4] = bf16_lo(v.z); vals[5] = bf16_hi(v.z);
+    vals[6] = bf16_lo(v.w); vals[7] = bf16_hi(v.w);
+  }
+};
+
+// f32: a 16-byte vector = 4 elements
+template <>
+struct Row<false> {
+  static constexpr int kElems = 4;
+  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
+    const f32x4 v = __builtin_nontemporal_load(static_cast<const f32x4*>(base) + row * row_vecs + c);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  }
+  __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
+    f32x4 v;
+    v.x = vals[0]; v.y = vals[1]; v.z = vals[2]; v.w = vals[3];
+    __builtin_nontemporal_store(v, static_cast<f32x4*>(base) + row * row_vecs + c);
+  }
+};
+
 constexpr int kWave = 64;
 constexpr int kPlanTokensPerBlock = 256;   // planner: one token per thread
 

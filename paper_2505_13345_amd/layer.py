@@ -1,4 +1,5 @@
-"""Device buffers for one layer and the call sequence of its forward hot path.
+"""Device buffers for one layer and the call sequence of its hot path (forward, and the backward
+pass of the data movement).
 
 Memory plumbing only: torch allocates the worst-case-sized buffers once (N_sfd <= T*min(k, D),
 N_epd = T*k), every step is one call into the C library on the current stream, and nothing here
@@ -83,6 +84,33 @@ class OccultLayer:
         self.expert_ffn(x, w_gate, w_up, w_down)
         self.combine()
         return self.y
+
+    # ---- backward of the data movement (buffers allocated on first use) -----------------------
+    def _buf(self, name, shape, dtype):
+        if getattr(self, name, None) is None:
+            setattr(self, name, torch.zeros(shape, dtype=dtype, device=self.device))
+        return getattr(self, name)
+
+    def combine_backward(self, dy, ids=None, epd_y=None, want_sfd=True, want_epd=True, want_dw=True):
+        """dy [T, d] -> sfd_dy, epd_dy, dw (each None if not asked for)."""
+        s = self.shape
+        sfd_dy = self._buf("sfd_dy", (self.n_sfd_max, s["d"]), self.tdtype) if want_sfd else None
+        epd_dy = self._buf("epd_dy", (s["T"] * s["k"], s["d"]), self.tdtype) if want_epd else None
+        dw = self._buf("dw", (s["T"], s["k"]), torch.float32) if want_dw else None
+        B.occult_combine_backward(self.cfg, self.plan, self.ids if ids is None else ids, dy,
+                                  self.epd_y if epd_y is None else epd_y, sfd_dy, epd_dy, dw)
+        return sfd_dy, epd_dy, dw
+
+    def dispatch_backward(self, epd_dx, dx_shared=None):
+        """epd_dx [T*k, d] -> sfd_dx, dx."""
+        s = self.shape
+        sfd_dx = self._buf("sfd_dx", (self.n_sfd_max, s["d"]), self.tdtype)
+        dx = self._buf("dx", (s["T"], s["d"]), self.tdtype)
+        B.occult_dispatch_backward(self.cfg, self.plan, epd_dx, sfd_dx, dx_shared, dx)
+        return sfd_dx, dx
+
+    def route_backward(self, logits, dw, dlogits, ids=None):
+        B.occult_route_backward(self.cfg, logits, self.ids if ids is None else ids, dw, dlogits)
 
     def stats(self):
         return B.occult_plan_stats(self.cfg, self.plan)
