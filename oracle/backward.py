@@ -1,5 +1,5 @@
-"""CPU oracle: backward pass of the layer's data movement (dispatch, row replication, two-stage
-merge, combine) and of the routing weights.
+"""CPU oracle: backward pass of the layer: its data movement (dispatch, row replication, two-stage
+merge, combine), its SwiGLU experts and its routing weights.
 
 TEST INFRASTRUCTURE ONLY (see oracle/routing.py for who may import this).
 
@@ -21,6 +21,9 @@ Readings (the paper is silent on all of them): the routing weight multiplies the
 row (for a linear down projection the same as multiplying the intermediate, which is where the
 forward oracle applies it); roundings of the forward pass are not differentiated; sums run over
 local experts in slot order, then over devices in ascending order, as in the forward pass.
+
+`expert_ffn_backward` is the chain rule through one SwiGLU expert (input and weight gradients);
+`layer_backward` strings the pieces together for the whole layer, shared experts included.
 
 `route_backward` is the gradient of the gate values of Eq. 1 with respect to the router scores:
 Softmax over all E experts, the values at the k selected experts, optionally divided by their sum.
@@ -134,3 +137,78 @@ def route_backward(logits, ids, g_w, renorm):
     np.add.at(g_p, (np.broadcast_to(rows, ids.shape), ids), g_sel)
     # softmax: d p_i / d l_j = p_i (delta_ij - p_j)
     return p * (g_p - (g_p * p).sum(axis=1, keepdims=True))
+
+
+def expert_ffn_backward(v, g_out, w_gate, w_up, w_down):
+    """Backward of one SwiGLU expert E(v) = W_down (silu(W_gate v) * (W_up v)) for rows v [n, d] and
+    output gradients g_out [n, d] (the forward is the expert of the baseline configuration; the
+    chain rule through it, nothing else).  Returns g_v [n, d] and the weight gradients
+    (g_w_gate [f, d], g_w_up [f, d], g_w_down [d, f]) summed over the rows."""
+    v = v.astype(np.float64)
+    g_out = g_out.astype(np.float64)
+    wg, wu, wd = (a.astype(np.float64) for a in (w_gate, w_up, w_down))
+    g = v @ wg.T
+    u = v @ wu.T
+    sig = 1.0 / (1.0 + np.exp(-g))
+    h = g * sig * u
+    g_h = g_out @ wd                                   # [n, f]
+    g_g = g_h * u * sig * (1.0 + g * (1.0 - sig))      # d silu(g) / d g = sig * (1 + g * (1 - sig))
+    g_u = g_h * g * sig
+    g_v = g_g @ wg + g_u @ wu
+    return g_v, (g_g.T @ v, g_u.T @ v, g_out.T @ h)
+
+
+def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
+    """Backward of the whole deduplicated layer, the forward pipeline walked in reverse on the same
+    re-index matrices: transposed Combine and merge, the experts' own backward per device and local
+    expert, transposed row gather and Dispatch; shared experts see every token with weight 1.
+    Returns a dict: g_x [T, d], g_w [T, k], g_w_gate / g_w_up / g_w_down like the weights, and the
+    intermediate payloads g_sfd_y, g_sfd_x."""
+    from . import occult_ref
+    T, d = x.shape
+    E = len(expert_pos)
+    tr = occult_ref.moe_forward(x, ids, w, expert_pos, D)
+    L = occult_ref.placement_lists(expert_pos, D)
+    offs = np.concatenate([[0], np.cumsum(tr.dev_count)])
+    # forward pieces that the backward needs: every expert's output rows, per device in local EPD order
+    out_epd = []
+    for j in range(D):
+        seg = tr.x_sfd[int(offs[j]):int(offs[j + 1])].astype(np.float64)
+        rows = np.zeros((int((tr.brim_1[j] >= 0).sum()), d))
+        for e, expert in enumerate(L[j]):
+            v = tr.brim_1[j][e]
+            present = v >= 0
+            if present.any():
+                g = seg[present] @ w_gate[expert].astype(np.float64).T
+                u = seg[present] @ w_up[expert].astype(np.float64).T
+                rows[v[present]] = (g / (1.0 + np.exp(-g)) * u) @ w_down[expert].astype(np.float64).T
+        out_epd.append(rows)
+    g_sfd_y, g_out, g_bw = combine_backward(g_y, out_epd, tr.brim_0, tr.brim_1, tr.brim_w, tr.dev_count)
+    g_wg = np.zeros(w_gate.shape)
+    g_wu = np.zeros(w_up.shape)
+    g_wd = np.zeros(w_down.shape)
+    g_in = []
+    for j in range(D):
+        seg = tr.x_sfd[int(offs[j]):int(offs[j + 1])]
+        rows = np.zeros_like(g_out[j])
+        for e, expert in enumerate(L[j]):
+            v = tr.brim_1[j][e]
+            present = v >= 0
+            if present.any():
+                g_v, (a, b, c) = expert_ffn_backward(seg[present], g_out[j][v[present]], w_gate[expert],
+                                                     w_up[expert], w_down[expert])
+                rows[v[present]] = g_v
+                g_wg[expert] += a
+                g_wu[expert] += b
+                g_wd[expert] += c
+        g_in.append(rows)
+    g_sfd_x, g_x = dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count)
+    for s in range(S):
+        g_v, (a, b, c) = expert_ffn_backward(x, g_y, w_gate[E + s], w_up[E + s], w_down[E + s])
+        g_x = g_x + g_v
+        g_wg[E + s] += a
+        g_wu[E + s] += b
+        g_wd[E + s] += c
+    return {"g_x": g_x, "g_w": gate_grad_to_slots(g_bw, ids, tr.brim_0, L, tr.dev_count),
+            "g_w_gate": g_wg, "g_w_up": g_wu, "g_w_down": g_wd, "g_sfd_y": g_sfd_y, "g_sfd_x": g_sfd_x,
+            "g_epd_x": g_in, "g_epd_y": g_out, "trace": tr}

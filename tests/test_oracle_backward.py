@@ -192,3 +192,89 @@ def test_route_backward_is_derivative_of_the_routing_oracle(renorm):
             assert np.array_equal(ids_p, ids) and np.array_equal(ids_m, ids)
             fd = np.sum(g_w * (w_p - w_m)) / (2 * float(h))
             assert g[t, e] == pytest.approx(fd, rel=2e-4, abs=1e-7)
+
+
+def _ffn_instance(seed, n, d, f):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((n, d)), rng.standard_normal((n, d)), rng.standard_normal((f, d)) / 2,
+            rng.standard_normal((f, d)) / 2, rng.standard_normal((d, f)) / 2)
+
+
+def test_expert_backward_matches_finite_differences_of_forward_oracle():
+    n, d, f = 4, 5, 6
+    v, g_out, wg, wu, wd = _ffn_instance(1, n, d, f)
+    g_v, (g_wg, g_wu, g_wd) = backward.expert_ffn_backward(v, g_out, wg, wu, wd)
+
+    def loss(vv, a, b, c):
+        return float(np.sum(g_out * moe_std.expert_ffn(vv, a, b, c)))
+
+    h = 1e-6
+
+    def numeric(arr, which):
+        out = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            e = np.zeros_like(arr)
+            e[idx] = h
+            args_p = [v, wg, wu, wd]
+            args_m = [v, wg, wu, wd]
+            args_p[which] = arr + e
+            args_m[which] = arr - e
+            out[idx] = (loss(*args_p) - loss(*args_m)) / (2 * h)
+        return out
+
+    assert np.allclose(g_v, numeric(v, 0), rtol=1e-6, atol=1e-7)
+    assert np.allclose(g_wg, numeric(wg, 1), rtol=1e-6, atol=1e-7)
+    assert np.allclose(g_wu, numeric(wu, 2), rtol=1e-6, atol=1e-7)
+    assert np.allclose(g_wd, numeric(wd, 3), rtol=1e-6, atol=1e-7)   # linear in w_down: exact up to rounding
+
+
+def test_expert_backward_closed_forms():
+    # gate pre-activation zero everywhere (w_gate = 0): silu(0) = 0 and silu'(0) = 1/2, so
+    # g_v = (1/2) * ((g_out W_down) * u) W_gate + 0 = 0 and only w_gate receives a gradient
+    n, d, f = 3, 4, 5
+    v, g_out, wg, wu, wd = _ffn_instance(2, n, d, f)
+    g_v, (g_wg, g_wu, g_wd) = backward.expert_ffn_backward(v, g_out, np.zeros_like(wg), wu, wd)
+    assert not g_v.any() and not g_wu.any() and not g_wd.any()
+    assert np.allclose(g_wg, (0.5 * (g_out @ wd) * (v @ wu.T)).T @ v, rtol=1e-13)
+    # large positive gate pre-activations: silu(g) -> g, the expert becomes W_down ((W_gate v) * (W_up v))
+    wg_big = np.abs(wg) + 1.0
+    v_pos = np.abs(v) + 5.0
+    g_v, _ = backward.expert_ffn_backward(v_pos, g_out, wg_big, wu, wd)
+    g = v_pos @ wg_big.T
+    u = v_pos @ wu.T
+    g_h = g_out @ wd
+    assert np.allclose(g_v, (g_h * u) @ wg_big + (g_h * g) @ wu, rtol=1e-6)
+
+
+@pytest.mark.parametrize("T,E,k,D,S", [(9, 8, 3, 4, 0), (7, 6, 2, 2, 2), (6, 4, 4, 4, 1)])
+def test_layer_backward_is_gradient_of_both_forward_oracles(T, E, k, D, S):
+    d, f = 5, 4
+    logits, pos, ids, w, x, g_y = _instance(T + E + S, T, E, k, D, d)
+    rng = np.random.default_rng(T)
+    wg = rng.standard_normal((E + S, f, d)) / 2
+    wu = rng.standard_normal((E + S, f, d)) / 2
+    wd = rng.standard_normal((E + S, d, f)) / 2
+    res = backward.layer_backward(x, ids, w, pos, D, wg, wu, wd, S, g_y)
+
+    def loss_occ(xx, ww, a, b, c):
+        return float(np.sum(g_y * occult_ref.moe_forward(xx, ids, ww, pos, D, a, b, c, S).y))
+
+    def loss_std(xx, ww, a, b, c):
+        return float(np.sum(g_y * moe_std.moe_layer(xx, ids, ww, a, b, c, E, S)))
+
+    h = 1e-6
+    for loss in (loss_occ, loss_std):
+        for name, which, arr in (("g_x", 0, x), ("g_w", 1, w), ("g_w_gate", 2, wg), ("g_w_up", 3, wu),
+                                 ("g_w_down", 4, wd)):
+            for trial in range(3):       # directional derivatives along random directions
+                v = np.random.default_rng(100 * which + trial).standard_normal(arr.shape)
+                args_p = [x, w, wg, wu, wd]
+                args_m = [x, w, wg, wu, wd]
+                args_p[which] = arr + h * v
+                args_m[which] = arr - h * v
+                fd = (loss(*args_p) - loss(*args_m)) / (2 * h)
+                assert np.sum(res[name] * v) == pytest.approx(fd, rel=2e-6, abs=1e-7), (name, trial)
+    # experts that no token selected receive no gradient
+    unused = sorted(set(range(E)) - set(ids.reshape(-1).tolist()))
+    for e in unused:
+        assert not res["g_w_gate"][e].any() and not res["g_w_down"][e].any()
