@@ -252,6 +252,31 @@ int occult_combine_backward(const occult_cfg_t* cfg, const occult_plan_t* plan, 
 int occult_dispatch_backward(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_dx,
                              void* sfd_dx, const void* dx_shared, void* dx, occult_stream_t stream);
 
+/* Backward of occult_expert_ffn with respect to the expert inputs (same sources as above; the chain
+ * rule through the SwiGLU expert on the same plan).
+ *
+ * occult_transpose_weights writes the two transposed weight copies the backward products read,
+ * device ptrs in cfg.dtype: w_down_t [E+S][f][d] = w_down^T and w_gu_t [E+S][d][2f] = [w_gate^T | w_up^T]
+ * side by side.  Call it again whenever the weights change.
+ *
+ * occult_expert_ffn_backward: for EPD row q of the expert at position P, x_q = sfd_x[epd_sfd_row[q]]:
+ *   g = W_gate x_q, u = W_up x_q (recomputed, rounded to cfg.dtype), dh = W_down^T epd_dy[q],
+ *   dg = dh * u * silu'(g), du = dh * silu(g), epd_dx[q] = W_gate^T dg + W_up^T du.
+ * epd_dy [N_epd][d] is occult_combine_backward's (gate-scaled) output.  Outputs: epd_dx [N_epd][d], and
+ * epd_gu [N_epd][2f] = [dg | du] (the operand a weight-gradient product needs); epd_dh [N_epd][f] is
+ * scratch.  Shared experts (S > 0; x [T][d], dy [T][d] = gradient of y_shared):
+ * gu_shared [T][S*2f] = per shared expert [dg | du], dh_shared [T][S*f] scratch,
+ * dx_shared [T][d] = sum over the shared experts of their input gradients (pass it to
+ * occult_dispatch_backward); all three may be NULL when S == 0.  Arithmetic as in the forward
+ * call: bf16 on MFMA with f32 accumulation, intermediates rounded to bf16; or plain f32. */
+int occult_transpose_weights(const occult_cfg_t* cfg, const occult_weights_t* weights, void* w_down_t,
+                             void* w_gu_t, occult_stream_t stream);
+int occult_expert_ffn_backward(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                               const void* x, const occult_weights_t* weights, const void* w_down_t,
+                               const void* w_gu_t, const void* epd_dy, const void* dy, void* epd_gu,
+                               void* epd_dh, void* epd_dx, void* gu_shared, void* dh_shared,
+                               void* dx_shared, occult_stream_t stream);
+
 /* Gradient of the routing weights with respect to the router scores (paper Eq. 1: Softmax over
  * all E experts, the values at the selected experts, divided by their sum if cfg.renorm; the
  * selection is piecewise constant and has no gradient).  logits [T][E] f32, ids [T][k] as returned

@@ -212,3 +212,34 @@ def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
     return {"g_x": g_x, "g_w": gate_grad_to_slots(g_bw, ids, tr.brim_0, L, tr.dev_count),
             "g_w_gate": g_wg, "g_w_up": g_wu, "g_w_down": g_wd, "g_sfd_y": g_sfd_y, "g_sfd_x": g_sfd_x,
             "g_epd_x": g_in, "g_epd_y": g_out, "trace": tr}
+
+
+def moe_layer_backward_tokens(x, ids, w, w_gate, w_up, w_down, E, S, g_y, tokens=None):
+    """Input and gate gradients of the textbook layer y[t] = sum_s w[t,s] E_{ids[t,s]}(x[t]) + shared,
+    for a subset of tokens (sampled parity at full size): a token's gradients depend on its own row
+    only.  Returns g_x [n, d] and g_w [n, k] for the n tokens, grouped by expert so that BLAS does
+    the products."""
+    if tokens is None:
+        tokens = np.arange(x.shape[0])
+    tokens = np.asarray(tokens)
+    xs = x[tokens].astype(np.float64)
+    gs = g_y[tokens].astype(np.float64)
+    ids_s = ids[tokens]
+    w_s = w[tokens].astype(np.float64)
+    g_x = np.zeros_like(xs)
+    g_w = np.zeros(ids_s.shape, dtype=np.float64)
+    for e in range(E):
+        rows, slots = np.nonzero(ids_s == e)
+        if rows.size == 0:
+            continue
+        v = xs[rows]
+        g_v, _ = expert_ffn_backward(v, w_s[rows, slots][:, None] * gs[rows], w_gate[e], w_up[e], w_down[e])
+        g_x[rows] += g_v
+        a = v @ w_gate[e].astype(np.float64).T
+        u = v @ w_up[e].astype(np.float64).T
+        out = (a / (1.0 + np.exp(-a)) * u) @ w_down[e].astype(np.float64).T
+        g_w[rows, slots] = np.einsum("rc,rc->r", gs[rows], out)
+    for s in range(S):
+        g_v, _ = expert_ffn_backward(xs, gs, w_gate[E + s], w_up[E + s], w_down[E + s])
+        g_x += g_v
+    return g_x, g_w

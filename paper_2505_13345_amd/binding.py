@@ -24,6 +24,7 @@ EXPORTS = [
     "occult_placement_greedy", "occult_plan_stats", "occult_router", "occult_dispatch_meta",
     "occult_similarity_gram", "occult_similarity_table", "occult_expert_ffn_ws_bytes", "occult_expert_ffn_ws",
     "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
+    "occult_transpose_weights", "occult_expert_ffn_backward",
 ]
 
 
@@ -94,6 +95,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                             c_void_p]
     lib.occult_dispatch_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_route_backward.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.occult_transpose_weights.argtypes = [cfgp, POINTER(occult_weights_t), c_void_p, c_void_p, c_void_p]
+    lib.occult_expert_ffn_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t)] + [c_void_p] * 11
     lib.occult_coactivation.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_placement_greedy.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
     lib.occult_plan_stats.argtypes = [cfgp, planp, POINTER(occult_stats_t), c_void_p]
@@ -232,6 +235,21 @@ def occult_dispatch_backward(cfg, plan, epd_dx, sfd_dx, dx_shared, dx, stream=No
 def occult_route_backward(cfg, logits, ids, dw, dlogits, stream=None) -> None:
     _check(load_library().occult_route_backward(ctypes.byref(cfg), _ptr(logits), _ptr(ids), _ptr(dw), _ptr(dlogits),
                                                 _stream(stream)))
+
+
+def occult_transpose_weights(cfg, w_gate, w_up, w_down, w_down_t, w_gu_t, stream=None) -> None:
+    wts = occult_weights_t(_ptr(w_gate), _ptr(w_up), _ptr(w_down))
+    _check(load_library().occult_transpose_weights(ctypes.byref(cfg), ctypes.byref(wts), _ptr(w_down_t), _ptr(w_gu_t),
+                                                   _stream(stream)))
+
+
+def occult_expert_ffn_backward(cfg, plan, sfd_x, x, w_gate, w_up, w_down_t, w_gu_t, epd_dy, dy, epd_gu, epd_dh, epd_dx,
+                               gu_shared=None, dh_shared=None, dx_shared=None, stream=None) -> None:
+    wts = occult_weights_t(_ptr(w_gate), _ptr(w_up), None)
+    _check(load_library().occult_expert_ffn_backward(ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x),
+                                                     ctypes.byref(wts), _ptr(w_down_t), _ptr(w_gu_t), _ptr(epd_dy),
+                                                     _ptr(dy), _ptr(epd_gu), _ptr(epd_dh), _ptr(epd_dx), _ptr(gu_shared),
+                                                     _ptr(dh_shared), _ptr(dx_shared), _stream(stream)))
 
 
 def occult_coactivation(cfg, ids, C, accumulate: bool = False, stream=None) -> None:

@@ -14,38 +14,12 @@
 // from LDS as 16-byte K-runs and no transpose is needed.
 // f32 path: plain f32 FMA kernel for small parity-sized layers.
 #include "common.h"
+#include "gemm.h"
 
 namespace occult {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-struct GemmArgs {
-  const void* A;            // activation rows, K-contiguous
-  int lda;                  // elements between A rows
-  const int32_t* a_rows;    // [rows] source row of each logical row, or NULL (identity)
-  const void* B;            // weights [group][N][kseg]
-  const void* B2;           // second weight matrix (up projection) when SWIGLU, same layout
-  long long b_group_stride; // elements between consecutive weight matrices
-  int ldb;                  // elements between B rows (= kseg)
-  int kseg;                 // K elements held by one weight matrix; K > kseg walks consecutive matrices
-  void* C;                  // output rows
-  int ldc;                  // elements between C rows
-  int c_col0;               // first output column written by group 0
-  int c_group_cols;         // group g writes from column c_col0 + g * c_group_cols
-  const int32_t* grp_offset;  // [ngroups+1] logical-row prefix per group, or NULL: every group takes rows [0, M)
-  const int32_t* grp_widx;    // [ngroups] weight matrix of each group, or NULL: w_base + group
-  int w_base;
-  int ngroups;
-  int M;                    // rows when grp_offset == NULL
-  int a_rows_total;         // rows of the A buffer that may be addressed (bounds 32-bit offsets)
-  int plain_map;            // small-tile kernel: workgroup id = m-tile * n_tiles + n-tile (tiny grids)
-  int ksplit;               // small-tile kernel, one group, no SWIGLU: blockIdx.y takes K tiles
-                            // [y*nk/ksplit, (y+1)*nk/ksplit) and writes f32 sums to ws; 0 or 1 = off
-  float* ws;                // [ksplit][M][N] partial sums
-  int N;                    // output columns (for SWIGLU: columns of h)
-  int K;
-};
 
 struct TileInfo {
   int group, m0, rows, row_base;
@@ -983,7 +957,7 @@ static int choose_ksplit(long long tiles, int nk) {
   return ks >= 2 ? (int)ks : 0;
 }
 
-static int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
+int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
   if (total_rows == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
     const int groups = a.ngroups;

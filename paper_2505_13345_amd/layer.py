@@ -109,6 +109,39 @@ class OccultLayer:
         B.occult_dispatch_backward(self.cfg, self.plan, epd_dx, sfd_dx, dx_shared, dx)
         return sfd_dx, dx
 
+    def transpose_weights(self, w_gate, w_up, w_down):
+        """Transposed weight copies for the backward products (again after every weight update)."""
+        s = self.shape
+        n = s["E"] + s["S"]
+        w_down_t = self._buf("w_down_t", (n, s["f"], s["d"]), self.tdtype)
+        w_gu_t = self._buf("w_gu_t", (n, s["d"], 2 * s["f"]), self.tdtype)
+        B.occult_transpose_weights(self.cfg, w_gate, w_up, w_down, w_down_t, w_gu_t)
+        return w_down_t, w_gu_t
+
+    def expert_ffn_backward(self, x, w_gate, w_up, epd_dy, dy):
+        """epd_dy [T*k, d] (and dy [T, d] for shared experts) -> epd_dx, dx_shared (None if S == 0);
+        needs transpose_weights() first and the forward's sfd_x."""
+        s = self.shape
+        T, k, d, f, S = s["T"], s["k"], s["d"], s["f"], s["S"]
+        epd_gu = self._buf("epd_gu", (T * k, 2 * f), self.tdtype)
+        epd_dh = self._buf("epd_dh", (T * k, f), self.tdtype)
+        epd_dx = self._buf("epd_dx", (T * k, d), self.tdtype)
+        gu_sh = dh_sh = dx_sh = None
+        if S > 0:
+            gu_sh = self._buf("gu_shared", (T, S * 2 * f), self.tdtype)
+            dh_sh = self._buf("dh_shared", (T, S * f), self.tdtype)
+            dx_sh = self._buf("dx_shared", (T, d), self.tdtype)
+        B.occult_expert_ffn_backward(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, self.w_down_t, self.w_gu_t,
+                                     epd_dy, dy, epd_gu, epd_dh, epd_dx, gu_sh, dh_sh, dx_sh)
+        return epd_dx, dx_sh
+
+    def backward_input(self, x, w_gate, w_up, dy):
+        """dy [T, d] -> dx [T, d], dw [T, k]: the three backward calls in order (after forward())."""
+        _, epd_dy, dw = self.combine_backward(dy, want_sfd=True)
+        epd_dx, dx_sh = self.expert_ffn_backward(x, w_gate, w_up, epd_dy, dy)
+        _, dx = self.dispatch_backward(epd_dx, dx_sh)
+        return dx, dw
+
     def route_backward(self, logits, dw, dlogits, ids=None):
         B.occult_route_backward(self.cfg, logits, self.ids if ids is None else ids, dw, dlogits)
 

@@ -1,0 +1,131 @@
+"""GPU parity for the backward pass of the expert computation and of the whole layer
+(occult_transpose_weights, occult_expert_ffn_backward, and the chain occult_combine_backward ->
+occult_expert_ffn_backward -> occult_dispatch_backward) against oracle/backward.py in float64.
+
+Bars.  f32: max |g - o| / max(|o|, rms(o)) <= 2e-5 (a chain of four f32 products and the SwiGLU
+derivative; the forward bar is 1e-5 for two products).  bf16: the chain rounds seven intermediates to
+bf16 (g, u, dh, dg, du, the EPD gradient rows, the SFD payload) besides the output, each 2^-9
+relative to a value of the order of the rms; the normalised maximum is held to 4e-2 and the mean
+absolute error to 4e-3 of the rms.
+"""
+import numpy as np
+import pytest
+import torch
+
+from inputs import workloads as wl
+from oracle import backward, routing
+from paper_2505_13345_amd.layer import OccultLayer
+from tests.helpers import f32_rel_error, require_gpu, say, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _mean_rel(got, want):
+    want = want.astype(np.float64)
+    return float(np.abs(got.astype(np.float64) - want).mean() / np.sqrt(np.mean(want ** 2)))
+
+
+def _check(name, got, want, dtype):
+    mx, mean = f32_rel_error(got, want), _mean_rel(got, want)
+    say(f"  {name}: normalised max {mx:.3e}, mean/rms {mean:.3e}")
+    if dtype == "f32":
+        assert mx <= 2e-5, name
+    else:
+        assert mx <= 4e-2 and mean <= 4e-3, name
+
+
+def _forward_backward(shape, wk, pos, dy):
+    dev = require_gpu()
+    layer = OccultLayer(shape.T, shape.d, shape.f, shape.E, shape.S, shape.k, shape.D, shape.dtype,
+                        shape.n_d, shape.prune_mode, shape.renorm, pos)
+    x = to_dev(wk.x, shape.dtype, dev)
+    wg, wu, wd = (to_dev(a, shape.dtype, dev) for a in (wk.w_gate, wk.w_up, wk.w_down))
+    layer.forward(torch.from_numpy(wk.logits).to(dev), x, wg, wu, wd)
+    w_down_t, w_gu_t = layer.transpose_weights(wg, wu, wd)
+    dx, dw = layer.backward_input(x, wg, wu, to_dev(dy, shape.dtype, dev))
+    torch.cuda.synchronize()
+    # the transposed copies, bit for bit
+    assert torch.equal(w_down_t, wd.transpose(1, 2).contiguous())
+    assert torch.equal(w_gu_t, torch.cat([wg.transpose(1, 2), wu.transpose(1, 2)], dim=2))
+    return layer, dx.float().cpu().numpy(), dw.cpu().numpy()
+
+
+SMALL = [
+    # name, T, d, f, E, S, k, D, dtype   (the forward test's shapes: every GEMM variant, ragged tails)
+    ("f32_a", 300, 96, 80, 8, 0, 2, 4, "f32"),
+    ("f32_shared", 130, 128, 256, 16, 2, 4, 4, "f32"),
+    ("bf16_a", 700, 256, 192, 8, 0, 2, 4, "bf16"),
+    ("bf16_shared", 333, 512, 320, 12, 2, 3, 3, "bf16"),
+    ("bf16_one_row_experts", 9, 128, 64, 16, 1, 2, 8, "bf16"),
+    ("bf16_big_expert", 1500, 192, 448, 4, 0, 1, 2, "bf16"),
+    ("bf16_few_rows_ragged", 80, 256, 192, 16, 2, 4, 4, "bf16"),
+    ("bf16_big_shared", 1100, 192, 128, 4, 3, 1, 4, "bf16"),
+]
+
+
+@pytest.mark.parametrize("name,T,d,f,E,S,k,D,dtype", SMALL)
+def test_small_layers_backward_elementwise(name, T, d, f, E, S, k, D, dtype):
+    say(f"small layer backward {name}")
+    shape = wl.LayerShape(name, T=T, d=d, f=f, E=E, S=S, k=k, D=D, dtype=dtype,
+                          components=4 if dtype == "bf16" else 0)
+    wk = wl.make_workload(shape, seed=17)
+    pos = wl.random_placement(E, D, seed=2)
+    dy = np.random.default_rng(T).standard_normal((T, d)).astype(np.float32)
+    if dtype == "bf16":
+        dy = wl.round_to_bf16(dy)
+    layer, dx, dw = _forward_backward(shape, wk, pos, dy)
+    ids, w = layer.ids.cpu().numpy(), layer.w.cpu().numpy().astype(np.float64)
+    ids_ref, _ = routing.route(wk.logits, k, D, pos)
+    assert np.array_equal(ids, ids_ref)
+    res = backward.layer_backward(wk.x, ids, w, pos, D, wk.w_gate, wk.w_up, wk.w_down, S, dy.astype(np.float64))
+    n_sfd = res["trace"].n_sfd
+    _check("epd_dy", layer.epd_dy.float().cpu().numpy(), np.concatenate(res["g_epd_y"]), dtype)
+    _check("epd_dx", layer.epd_dx.float().cpu().numpy(), np.concatenate(res["g_epd_x"]), dtype)
+    _check("sfd_dx", layer.sfd_dx[:n_sfd].float().cpu().numpy(), res["g_sfd_x"], dtype)
+    _check("dx", dx, res["g_x"], dtype)
+    _check("dw", dw, res["g_w"], dtype)
+    assert np.array_equal(layer.sfd_dy[:n_sfd].float().cpu().numpy(), res["g_sfd_y"])   # a copy of dy rows
+
+
+def _sampled_backward(name, n_sample=128):
+    shape = wl.CONFIGS[name]
+    say(f"{name}: generating")
+    wk = wl.make_workload(shape)
+    g = np.random.default_rng(5)
+    dy = wl.round_to_bf16(g.standard_normal((shape.T, shape.d), dtype=np.float32))
+    say(f"{name}: forward + backward on GPU")
+    layer, dx, dw = _forward_backward(shape, wk, None, dy)
+    ids, w = layer.ids.cpu().numpy(), layer.w.cpu().numpy().astype(np.float64)
+    rng = np.random.default_rng(123)
+    tokens = np.sort(rng.choice(shape.T, size=min(n_sample, shape.T), replace=False))
+    tokens[0], tokens[-1] = 0, shape.T - 1
+    say(f"{name}: oracle on {len(tokens)} sampled tokens")
+    g_x, g_w = backward.moe_layer_backward_tokens(wk.x, ids, w, wk.w_gate, wk.w_up, wk.w_down, shape.E, shape.S,
+                                                  dy, tokens)
+    _check("dx (sampled)", dx[tokens], g_x, "bf16")
+    _check("dw (sampled)", dw[tokens], g_w, "bf16")
+    assert np.isfinite(dx).all() and np.isfinite(dw).all()
+
+
+def test_decode_config_backward():
+    _sampled_backward("decode_bf16")
+
+
+def test_prefill_config_backward_sampled():
+    _sampled_backward("prefill_bf16")
+
+
+def test_ffn_backward_argument_checks():
+    from paper_2505_13345_amd import binding as B
+    dev = require_gpu()
+    layer = OccultLayer(8, 64, 64, 4, 1, 2, 2, "bf16")
+    z = torch.zeros((64, 64), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(B.OccultError) as e:   # shared experts need their buffers
+        B.occult_expert_ffn_backward(layer.cfg, layer.plan, z, z, z, z, z, z, z, z, z, z, z, None, None, None)
+    assert e.value.code == -4
+    with pytest.raises(B.OccultError) as e:
+        B.occult_transpose_weights(layer.cfg, z, z, z, None, z)
+    assert e.value.code == -4
+    empty = OccultLayer(0, 64, 64, 4, 0, 2, 2, "bf16")
+    B.occult_expert_ffn_backward(empty.cfg, empty.plan, None, None, None, None, None, None, None, None, None, None, None)
+    torch.cuda.synchronize()

@@ -278,3 +278,17 @@ def test_layer_backward_is_gradient_of_both_forward_oracles(T, E, k, D, S):
     unused = sorted(set(range(E)) - set(ids.reshape(-1).tolist()))
     for e in unused:
         assert not res["g_w_gate"][e].any() and not res["g_w_down"][e].any()
+
+
+def test_per_token_backward_equals_the_pipeline_backward():
+    T, E, k, D, S, d, f = 14, 8, 3, 4, 1, 5, 4
+    logits, pos, ids, w, x, g_y = _instance(77, T, E, k, D, d)
+    rng = np.random.default_rng(6)
+    wg = rng.standard_normal((E + S, f, d)) / 2
+    wu = rng.standard_normal((E + S, f, d)) / 2
+    wd = rng.standard_normal((E + S, d, f)) / 2
+    res = backward.layer_backward(x, ids, w, pos, D, wg, wu, wd, S, g_y)
+    tokens = np.array([0, 3, 4, 9, 13])
+    g_x, g_w = backward.moe_layer_backward_tokens(x, ids, w, wg, wu, wd, E, S, g_y, tokens)
+    assert np.allclose(g_x, res["g_x"][tokens], rtol=1e-11, atol=1e-12)
+    assert np.allclose(g_w, res["g_w"][tokens], rtol=1e-11, atol=1e-12)
