@@ -277,6 +277,21 @@ int occult_expert_ffn_backward(const occult_cfg_t* cfg, const occult_plan_t* pla
                                void* epd_dh, void* epd_dx, void* gu_shared, void* dh_shared,
                                void* dx_shared, occult_stream_t stream);
 
+/* Weight gradients of occult_expert_ffn (same sources; f32 outputs in the layout of the weights:
+ * dw_gate, dw_up [E+S][f][d], dw_down [E+S][d][f], device ptrs).  For the expert at position P with
+ * EPD rows q in [exp_offset[P], exp_offset[P+1]) and x_q = sfd_x[epd_sfd_row[q]]:
+ *   dw_down = sum_q epd_dy[q] (x) epd_h[q],  dw_gate = sum_q dg[q] (x) x_q,  dw_up = sum_q du[q] (x) x_q,
+ * rows summed in f32 (bf16: MFMA, rows in blocks of 64 in ascending order; order-fixed, no atomics).
+ * Inputs: epd_h (and h_shared) as left by occult_expert_ffn, epd_dy by occult_combine_backward,
+ * epd_gu = [dg | du] (and gu_shared) by occult_expert_ffn_backward; dy [T][d] serves the shared
+ * experts.  accumulate = 0 overwrites the three outputs (experts without rows get zeros), 1 adds to
+ * them (gradient accumulation over micro-batches).  A plan built for T == 0 writes zeros / adds nothing. */
+int occult_expert_ffn_backward_weights(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                       const void* x, const void* epd_h, const void* h_shared,
+                                       const void* epd_dy, const void* dy, const void* epd_gu,
+                                       const void* gu_shared, float* dw_gate, float* dw_up, float* dw_down,
+                                       int accumulate, occult_stream_t stream);
+
 /* Gradient of the routing weights with respect to the router scores (paper Eq. 1: Softmax over
  * all E experts, the values at the selected experts, divided by their sum if cfg.renorm; the
  * selection is piecewise constant and has no gradient).  logits [T][E] f32, ids [T][k] as returned

@@ -139,11 +139,12 @@ def route_backward(logits, ids, g_w, renorm):
     return p * (g_p - (g_p * p).sum(axis=1, keepdims=True))
 
 
-def expert_ffn_backward(v, g_out, w_gate, w_up, w_down):
+def expert_ffn_backward(v, g_out, w_gate, w_up, w_down, with_pre=False):
     """Backward of one SwiGLU expert E(v) = W_down (silu(W_gate v) * (W_up v)) for rows v [n, d] and
     output gradients g_out [n, d] (the forward is the expert of the baseline configuration; the
     chain rule through it, nothing else).  Returns g_v [n, d] and the weight gradients
-    (g_w_gate [f, d], g_w_up [f, d], g_w_down [d, f]) summed over the rows."""
+    (g_w_gate [f, d], g_w_up [f, d], g_w_down [d, f]) summed over the rows; ``with_pre`` appends the
+    gradients of the two pre-activations, [g_gate | g_up] as rows of 2f."""
     v = v.astype(np.float64)
     g_out = g_out.astype(np.float64)
     wg, wu, wd = (a.astype(np.float64) for a in (w_gate, w_up, w_down))
@@ -155,6 +156,8 @@ def expert_ffn_backward(v, g_out, w_gate, w_up, w_down):
     g_g = g_h * u * sig * (1.0 + g * (1.0 - sig))      # d silu(g) / d g = sig * (1 + g * (1 - sig))
     g_u = g_h * g * sig
     g_v = g_g @ wg + g_u @ wu
+    if with_pre:
+        return g_v, (g_g.T @ v, g_u.T @ v, g_out.T @ h), np.concatenate([g_g, g_u], axis=1)
     return g_v, (g_g.T @ v, g_u.T @ v, g_out.T @ h)
 
 
@@ -163,7 +166,7 @@ def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
     re-index matrices: transposed Combine and merge, the experts' own backward per device and local
     expert, transposed row gather and Dispatch; shared experts see every token with weight 1.
     Returns a dict: g_x [T, d], g_w [T, k], g_w_gate / g_w_up / g_w_down like the weights, and the
-    intermediate payloads g_sfd_y, g_sfd_x."""
+    intermediate payloads g_sfd_y, g_sfd_x and per-device EPD rows g_epd_y, g_epd_gu ([g_gate | g_up]), g_epd_x."""
     from . import occult_ref
     T, d = x.shape
     E = len(expert_pos)
@@ -187,21 +190,24 @@ def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
     g_wg = np.zeros(w_gate.shape)
     g_wu = np.zeros(w_up.shape)
     g_wd = np.zeros(w_down.shape)
-    g_in = []
+    g_in, g_pre = [], []
     for j in range(D):
         seg = tr.x_sfd[int(offs[j]):int(offs[j + 1])]
         rows = np.zeros_like(g_out[j])
+        pre = np.zeros((g_out[j].shape[0], 2 * w_gate.shape[1]))
         for e, expert in enumerate(L[j]):
             v = tr.brim_1[j][e]
             present = v >= 0
             if present.any():
-                g_v, (a, b, c) = expert_ffn_backward(seg[present], g_out[j][v[present]], w_gate[expert],
-                                                     w_up[expert], w_down[expert])
+                g_v, (a, b, c), gu = expert_ffn_backward(seg[present], g_out[j][v[present]], w_gate[expert],
+                                                         w_up[expert], w_down[expert], with_pre=True)
                 rows[v[present]] = g_v
+                pre[v[present]] = gu
                 g_wg[expert] += a
                 g_wu[expert] += b
                 g_wd[expert] += c
         g_in.append(rows)
+        g_pre.append(pre)
     g_sfd_x, g_x = dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count)
     for s in range(S):
         g_v, (a, b, c) = expert_ffn_backward(x, g_y, w_gate[E + s], w_up[E + s], w_down[E + s])
@@ -211,7 +217,7 @@ def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
         g_wd[E + s] += c
     return {"g_x": g_x, "g_w": gate_grad_to_slots(g_bw, ids, tr.brim_0, L, tr.dev_count),
             "g_w_gate": g_wg, "g_w_up": g_wu, "g_w_down": g_wd, "g_sfd_y": g_sfd_y, "g_sfd_x": g_sfd_x,
-            "g_epd_x": g_in, "g_epd_y": g_out, "trace": tr}
+            "g_epd_x": g_in, "g_epd_y": g_out, "g_epd_gu": g_pre, "trace": tr}
 
 
 def moe_layer_backward_tokens(x, ids, w, w_gate, w_up, w_down, E, S, g_y, tokens=None):

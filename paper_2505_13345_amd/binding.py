@@ -24,7 +24,7 @@ EXPORTS = [
     "occult_placement_greedy", "occult_plan_stats", "occult_router", "occult_dispatch_meta",
     "occult_similarity_gram", "occult_similarity_table", "occult_expert_ffn_ws_bytes", "occult_expert_ffn_ws",
     "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
-    "occult_transpose_weights", "occult_expert_ffn_backward",
+    "occult_transpose_weights", "occult_expert_ffn_backward", "occult_expert_ffn_backward_weights",
 ]
 
 
@@ -97,6 +97,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_route_backward.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_transpose_weights.argtypes = [cfgp, POINTER(occult_weights_t), c_void_p, c_void_p, c_void_p]
     lib.occult_expert_ffn_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t)] + [c_void_p] * 11
+    lib.occult_expert_ffn_backward_weights.argtypes = [cfgp, planp] + [c_void_p] * 11 + [c_int, c_void_p]
     lib.occult_coactivation.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_placement_greedy.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
     lib.occult_plan_stats.argtypes = [cfgp, planp, POINTER(occult_stats_t), c_void_p]
@@ -250,6 +251,13 @@ def occult_expert_ffn_backward(cfg, plan, sfd_x, x, w_gate, w_up, w_down_t, w_gu
                                                      ctypes.byref(wts), _ptr(w_down_t), _ptr(w_gu_t), _ptr(epd_dy),
                                                      _ptr(dy), _ptr(epd_gu), _ptr(epd_dh), _ptr(epd_dx), _ptr(gu_shared),
                                                      _ptr(dh_shared), _ptr(dx_shared), _stream(stream)))
+
+
+def occult_expert_ffn_backward_weights(cfg, plan, sfd_x, x, epd_h, h_shared, epd_dy, dy, epd_gu, gu_shared, dw_gate,
+                                       dw_up, dw_down, accumulate=False, stream=None) -> None:
+    _check(load_library().occult_expert_ffn_backward_weights(
+        ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x), _ptr(epd_h), _ptr(h_shared), _ptr(epd_dy), _ptr(dy),
+        _ptr(epd_gu), _ptr(gu_shared), _ptr(dw_gate), _ptr(dw_up), _ptr(dw_down), int(bool(accumulate)), _stream(stream)))
 
 
 def occult_coactivation(cfg, ids, C, accumulate: bool = False, stream=None) -> None:

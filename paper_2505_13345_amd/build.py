@@ -19,7 +19,7 @@ OBJ_DIR = os.path.join(ROOT, "_build", "occult")
 LIB_PATH = os.path.join(HERE, "liboccult.so")
 
 SOURCES = ["api.hip", "route.hip", "plan.hip", "dispatch.hip", "ffn.hip", "combine.hip", "coact.hip", "backward.hip",
-           "ffn_backward.hip"]
+           "ffn_backward.hip", "wgrad.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -135,6 +135,18 @@ class OccultLayer:
                                      epd_dy, dy, epd_gu, epd_dh, epd_dx, gu_sh, dh_sh, dx_sh)
         return epd_dx, dx_sh
 
+    def expert_ffn_backward_weights(self, x, dy, accumulate=False):
+        """f32 weight gradients dw_gate, dw_up [E+S, f, d], dw_down [E+S, d, f]; after expert_ffn_backward()."""
+        s = self.shape
+        n = s["E"] + s["S"]
+        dw_gate = self._buf("dw_gate", (n, s["f"], s["d"]), torch.float32)
+        dw_up = self._buf("dw_up", (n, s["f"], s["d"]), torch.float32)
+        dw_down = self._buf("dw_down", (n, s["d"], s["f"]), torch.float32)
+        B.occult_expert_ffn_backward_weights(self.cfg, self.plan, self.sfd_x, x, self.epd_h, self.h_shared, self.epd_dy,
+                                             dy, self.epd_gu, getattr(self, "gu_shared", None), dw_gate, dw_up, dw_down,
+                                             accumulate)
+        return dw_gate, dw_up, dw_down
+
     def backward_input(self, x, w_gate, w_up, dy):
         """dy [T, d] -> dx [T, d], dw [T, k]: the three backward calls in order (after forward())."""
         _, epd_dy, dw = self.combine_backward(dy, want_sfd=True)

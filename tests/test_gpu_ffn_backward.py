@@ -34,6 +34,59 @@ def _check(name, got, want, dtype):
         assert mx <= 4e-2 and mean <= 4e-3, name
 
 
+def _check_weight_grads_on_stored_operands(layer, shape, x_np, dy_np, positions):
+    """The three products of occult_expert_ffn_backward_weights written out on the library's own
+    stored operands (each of them compared with the oracle elsewhere in this file), in float64:
+    pins the kernel's own arithmetic (f32 accumulation over an expert's rows) tightly."""
+    tabs = layer.tables()
+    exp_off = tabs["exp_offset"].cpu().numpy()
+    pos_expert = tabs["pos_expert"].cpu().numpy()
+    src = tabs["epd_sfd_row"].long()
+    f = shape.f
+    for P in positions:
+        q0, q1 = int(exp_off[P]), int(exp_off[P + 1])
+        e = int(pos_expert[P])
+        dyq = layer.epd_dy[q0:q1].double()
+        gu = layer.epd_gu[q0:q1].double()
+        xq = layer.sfd_x[src[q0:q1]].double()
+        for name, want in (("dw_down", dyq.T @ layer.epd_h[q0:q1].double()), ("dw_gate", gu[:, :f].T @ xq),
+                           ("dw_up", gu[:, f:].T @ xq)):
+            got = getattr(layer, name)[e].cpu().numpy()
+            if q1 == q0:
+                assert not got.any(), (name, P)
+            else:
+                assert f32_rel_error(got, want.cpu().numpy()) <= 1e-5, (name, P)
+    xs = torch.from_numpy(x_np).to(layer.device).double()
+    dys = torch.from_numpy(dy_np).to(layer.device).double()
+    for sidx in range(shape.S):
+        e = shape.E + sidx
+        gu = layer.gu_shared[:, sidx * 2 * f:(sidx + 1) * 2 * f].double()
+        want = dys.T @ layer.h_shared[:, sidx * f:(sidx + 1) * f].double()
+        assert f32_rel_error(layer.dw_down[e].cpu().numpy(), want.cpu().numpy()) <= 1e-5
+        assert f32_rel_error(layer.dw_gate[e].cpu().numpy(), (gu[:, :f].T @ xs).cpu().numpy()) <= 1e-5
+        assert f32_rel_error(layer.dw_up[e].cpu().numpy(), (gu[:, f:].T @ xs).cpu().numpy()) <= 1e-5
+
+
+def _check_per_matrix(name, got, want, dtype):
+    """Weight gradients: every expert's matrix against the oracle's, normalised by that matrix's own rms
+    (experts differ widely in their number of rows, and so in the size of their gradients and errors)."""
+    worst_mx = worst_mean = 0.0
+    for e in range(want.shape[0]):
+        if not want[e].any():
+            assert not got[e].any(), (name, e)
+            continue
+        worst_mx = max(worst_mx, f32_rel_error(got[e], want[e]))
+        worst_mean = max(worst_mean, _mean_rel(got[e], want[e]))
+    say(f"  {name}: worst expert normalised max {worst_mx:.3e}, mean/rms {worst_mean:.3e}")
+    if dtype == "f32":
+        assert worst_mx <= 2e-5, name
+    else:
+        # an element's error grows with the size of its operands' columns (hidden-state columns differ several
+        # times in magnitude), not with its own value, so the normalised maximum has a long tail: the mean is
+        # the bar that bites here; the product itself is pinned to 1e-5 on the stored operands below
+        assert worst_mx <= 1.5e-1 and worst_mean <= 4e-3, name
+
+
 def _forward_backward(shape, wk, pos, dy):
     dev = require_gpu()
     layer = OccultLayer(shape.T, shape.d, shape.f, shape.E, shape.S, shape.k, shape.D, shape.dtype,
@@ -42,7 +95,9 @@ def _forward_backward(shape, wk, pos, dy):
     wg, wu, wd = (to_dev(a, shape.dtype, dev) for a in (wk.w_gate, wk.w_up, wk.w_down))
     layer.forward(torch.from_numpy(wk.logits).to(dev), x, wg, wu, wd)
     w_down_t, w_gu_t = layer.transpose_weights(wg, wu, wd)
-    dx, dw = layer.backward_input(x, wg, wu, to_dev(dy, shape.dtype, dev))
+    dy_d = to_dev(dy, shape.dtype, dev)
+    dx, dw = layer.backward_input(x, wg, wu, dy_d)
+    layer.expert_ffn_backward_weights(x, dy_d)
     torch.cuda.synchronize()
     # the transposed copies, bit for bit
     assert torch.equal(w_down_t, wd.transpose(1, 2).contiguous())
@@ -80,11 +135,22 @@ def test_small_layers_backward_elementwise(name, T, d, f, E, S, k, D, dtype):
     res = backward.layer_backward(wk.x, ids, w, pos, D, wk.w_gate, wk.w_up, wk.w_down, S, dy.astype(np.float64))
     n_sfd = res["trace"].n_sfd
     _check("epd_dy", layer.epd_dy.float().cpu().numpy(), np.concatenate(res["g_epd_y"]), dtype)
+    _check("epd_gu", layer.epd_gu.float().cpu().numpy(), np.concatenate(res["g_epd_gu"]), dtype)
     _check("epd_dx", layer.epd_dx.float().cpu().numpy(), np.concatenate(res["g_epd_x"]), dtype)
     _check("sfd_dx", layer.sfd_dx[:n_sfd].float().cpu().numpy(), res["g_sfd_x"], dtype)
     _check("dx", dx, res["g_x"], dtype)
     _check("dw", dw, res["g_w"], dtype)
     assert np.array_equal(layer.sfd_dy[:n_sfd].float().cpu().numpy(), res["g_sfd_y"])   # a copy of dy rows
+    # weight gradients (f32 outputs; their inputs carry the roundings of the chain above)
+    grads = {n: getattr(layer, n).cpu().numpy() for n in ("dw_gate", "dw_up", "dw_down")}
+    for n, ref in (("dw_gate", "g_w_gate"), ("dw_up", "g_w_up"), ("dw_down", "g_w_down")):
+        _check_per_matrix(n, grads[n], res[ref], dtype)   # experts without rows: exact zeros
+    _check_weight_grads_on_stored_operands(layer, shape, wk.x, dy, range(E))
+    # accumulate = 1 adds the same product again: exactly twice the first result
+    layer.expert_ffn_backward_weights(to_dev(wk.x, dtype, require_gpu()), to_dev(dy, dtype, require_gpu()), accumulate=True)
+    torch.cuda.synchronize()
+    for n in grads:
+        assert np.array_equal(getattr(layer, n).cpu().numpy(), 2 * grads[n]), n
 
 
 def _sampled_backward(name, n_sample=128):
@@ -105,6 +171,7 @@ def _sampled_backward(name, n_sample=128):
     _check("dx (sampled)", dx[tokens], g_x, "bf16")
     _check("dw (sampled)", dw[tokens], g_w, "bf16")
     assert np.isfinite(dx).all() and np.isfinite(dw).all()
+    _check_weight_grads_on_stored_operands(layer, shape, wk.x, dy, sorted({0, shape.E // 2, shape.E - 1}))
 
 
 def test_decode_config_backward():
