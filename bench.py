@@ -260,10 +260,25 @@ def main():
             "dispatch_backward": (n_epd + n_sfd + T) * row,
             "route_backward": T * (2 * shape.E * 4 + k * 8),
         }
+        # backward of the expert computation: input gradients (5 products of 2*d*f flops per row, the forward has 3)
+        # and weight gradients (3 products)
+        layer.transpose_weights(wg, wu, wd)
+        layer.expert_ffn_backward(x, wg, wu, layer.epd_dy, dy)
+        layer.expert_ffn_backward_weights(x, dy)
+        bc["transpose_weights"] = _event_time_ms(lambda: layer.transpose_weights(wg, wu, wd), r)
+        bc["expert_ffn_backward"] = _event_time_ms(lambda: layer.expert_ffn_backward(x, wg, wu, layer.epd_dy, dy), r)
+        bc["expert_ffn_backward_weights"] = _event_time_ms(lambda: layer.expert_ffn_backward_weights(x, dy), r)
+        rows_ffn = n_epd + S * T
+        fb = {"expert_ffn_backward": 10.0 * d * f * rows_ffn, "expert_ffn_backward_weights": 6.0 * d * f * rows_ffn}
+        bb["transpose_weights"] = 2.0 * 3 * (shape.E + S) * d * f * es
         backward = {"calls_ms": bc,
                     "rooflines": {n: {"bound": "hbm", "achieved": gbs(bb[n], bc[n]), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                      "frac": gbs(bb[n], bc[n]) / PEAK_HBM_GBS} for n in bc}}
-        for n in ("sfd_dy", "epd_dy", "sfd_dx", "dx", "dw"):
+                                      "frac": gbs(bb[n], bc[n]) / PEAK_HBM_GBS} for n in bb}}
+        for n in fb:
+            backward["rooflines"][n] = {"bound": "mfma", "achieved": tf(fb[n], bc[n]), "peak": PEAK_BF16_TFLOPS,
+                                        "unit": "TFLOP/s", "frac": tf(fb[n], bc[n]) / PEAK_BF16_TFLOPS}
+        for n in ("sfd_dy", "epd_dy", "sfd_dx", "dx", "dw", "w_down_t", "w_gu_t", "epd_gu", "epd_dh", "epd_dx", "gu_shared",
+                  "dh_shared", "dx_shared", "dw_gate", "dw_up", "dw_down"):
             setattr(layer, n, None)
         del dy, dlogits
         torch.cuda.empty_cache()

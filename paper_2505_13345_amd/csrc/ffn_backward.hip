@@ -39,6 +39,41 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
   }
 }
 
+// The same for 2-byte elements with 16-byte global accesses on both sides (R % 8 == 0, C % 8 == 0):
+// a thread loads 8 columns of two rows, scatters them into the LDS tile as [column][row], and reads
+// back 8 consecutive rows of one column as one vector.  LDS rows are padded to 72 elements (144
+// bytes), which keeps the vectors 16-byte aligned.
+__global__ __launch_bounds__(256) void transpose16_kernel(const unsigned short* __restrict__ in,
+                                                          unsigned short* __restrict__ out, int R, int C,
+                                                          long long out_mat_stride, int out_ld, int col0) {
+  __shared__ __attribute__((aligned(16))) unsigned short tile[64][72];
+  const int m = blockIdx.z;
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const unsigned short* src = in + (size_t)m * R * C;
+  unsigned short* dst = out + (size_t)m * out_mat_stride;
+  const int v = threadIdx.x & 7, q = threadIdx.x >> 3;   // vector of 8 inside 64, row (or column) 0..31
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int r = r0 + q + 32 * h, c = c0 + v * 8;
+    if (r < R && c < C) {
+      const u32x4 x = *reinterpret_cast<const u32x4*>(src + (size_t)r * C + c);
+      const unsigned w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        tile[v * 8 + 2 * j][q + 32 * h] = (unsigned short)(w[j] & 0xFFFFu);
+        tile[v * 8 + 2 * j + 1][q + 32 * h] = (unsigned short)(w[j] >> 16);
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int c = c0 + q + 32 * h, r = r0 + v * 8;
+    if (r < R && c < C)
+      *reinterpret_cast<u32x4*>(dst + (size_t)c * out_ld + col0 + r) = *reinterpret_cast<const u32x4*>(&tile[q + 32 * h][v * 8]);
+  }
+}
+
 // gu[row] = [g | u] (2f elements), dh[row] (f elements)  ->  gu[row] = [dg | du], in place.
 // One thread per 16-byte vector of a row of f elements.
 template <bool BF16>
@@ -79,23 +114,30 @@ static int launch_swiglu_bwd(const occult_cfg_t& c, void* gu, const void* dh, lo
   return OCCULT_OK;
 }
 
-template <typename T>
-static int launch_transposes(const occult_cfg_t& c, const occult_weights_t* w, void* w_down_t, void* w_gu_t,
-                             hipStream_t s) {
-  const int n = c.E + c.S;
-  const dim3 block(256);
-  // w_down [n][d][f] -> [n][f][d]
-  hipLaunchKernelGGL(transpose_kernel<T>, dim3((c.f + 63) / 64, (c.d + 63) / 64, n), block, 0, s,
-                     static_cast<const T*>(w->w_down), static_cast<T*>(w_down_t), c.d, c.f, (long long)c.f * c.d, c.d, 0);
-  OCC_LAUNCH_CHECK("transpose_kernel");
-  // w_gate, w_up [n][f][d] -> [n][d][2f], gate in columns [0, f), up in [f, 2f)
-  hipLaunchKernelGGL(transpose_kernel<T>, dim3((c.d + 63) / 64, (c.f + 63) / 64, n), block, 0, s,
-                     static_cast<const T*>(w->w_gate), static_cast<T*>(w_gu_t), c.f, c.d, 2ll * c.f * c.d, 2 * c.f, 0);
-  OCC_LAUNCH_CHECK("transpose_kernel");
-  hipLaunchKernelGGL(transpose_kernel<T>, dim3((c.d + 63) / 64, (c.f + 63) / 64, n), block, 0, s,
-                     static_cast<const T*>(w->w_up), static_cast<T*>(w_gu_t), c.f, c.d, 2ll * c.f * c.d, 2 * c.f, c.f);
+// in [n][R][C] -> out[m][c][col0 + r]
+static int launch_transpose(const occult_cfg_t& c, const void* in, void* out, int R, int C, long long out_mat_stride,
+                            int out_ld, int col0, hipStream_t s) {
+  const dim3 grid((C + 63) / 64, (R + 63) / 64, c.E + c.S), block(256);
+  if (c.dtype == OCCULT_BF16)   // d and f are multiples of 8 (16-byte rows), so every vector is whole and aligned
+    hipLaunchKernelGGL(transpose16_kernel, grid, block, 0, s, static_cast<const unsigned short*>(in),
+                       static_cast<unsigned short*>(out), R, C, out_mat_stride, out_ld, col0);
+  else
+    hipLaunchKernelGGL(transpose_kernel<float>, grid, block, 0, s, static_cast<const float*>(in),
+                       static_cast<float*>(out), R, C, out_mat_stride, out_ld, col0);
   OCC_LAUNCH_CHECK("transpose_kernel");
   return OCCULT_OK;
+}
+
+static int launch_transposes(const occult_cfg_t& c, const occult_weights_t* w, void* w_down_t, void* w_gu_t,
+                             hipStream_t s) {
+  const long long mat = (long long)c.f * c.d;
+  // w_down [n][d][f] -> [n][f][d]
+  int rc = launch_transpose(c, w->w_down, w_down_t, c.d, c.f, mat, c.d, 0, s);
+  if (rc) return rc;
+  // w_gate, w_up [n][f][d] -> [n][d][2f], gate in columns [0, f), up in [f, 2f)
+  rc = launch_transpose(c, w->w_gate, w_gu_t, c.f, c.d, 2 * mat, 2 * c.f, 0, s);
+  if (rc) return rc;
+  return launch_transpose(c, w->w_up, w_gu_t, c.f, c.d, 2 * mat, 2 * c.f, c.f, s);
 }
 
 static int check_ffn_shapes(const occult_cfg_t& c) {
@@ -121,9 +163,13 @@ extern "C" int occult_transpose_weights(const occult_cfg_t* cfg, const occult_we
               "weights or one of its tensors is NULL");
   OCC_REQUIRE(w_down_t && w_gu_t, OCCULT_ENULLPTR, "w_down_t or w_gu_t is NULL");
   OCC_REQUIRE((c.E + c.S) <= 65535, OCCULT_EINVAL, "too many weight matrices");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (c.dtype == OCCULT_BF16) return launch_transposes<unsigned short>(c, weights, w_down_t, w_gu_t, s);
-  return launch_transposes<float>(c, weights, w_down_t, w_gu_t, s);
+  const int es = elem_size(c);
+  OCC_REQUIRE(((size_t)c.d * es) % 16 == 0 && ((size_t)c.f * es) % 16 == 0, OCCULT_EALIGN,
+              "rows of d=%d or f=%d elements are not multiples of 16 bytes", c.d, c.f);
+  OCC_REQUIRE(aligned16(weights->w_gate) && aligned16(weights->w_up) && aligned16(weights->w_down) &&
+                  aligned16(w_down_t) && aligned16(w_gu_t),
+              OCCULT_EALIGN, "a buffer is not 16-byte aligned");
+  return launch_transposes(c, weights, w_down_t, w_gu_t, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int occult_expert_ffn_backward(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,

@@ -9,19 +9,11 @@
 // ROW index of two row-major operands, the one GEMM shape the forward kernels do not cover (their
 // operands are both contiguous along the contracted index).
 //
-// bf16 kernel.  Block = 256 threads = 4 waves (2 x 2), block tile 256 x 256 outputs, wave tile
-// 128 x 128 = 4 x 4 v_mfma_f32_32x32x16_bf16 tiles (256 accumulator registers, one block per CU),
-// 64 rows per step.  The MFMA operands want 8 consecutive contracted elements per lane, which in
-// memory are 8 different rows: a thread loads 16-byte vectors (8 columns) of 4 consecutive rows,
-// transposes the 4 x 8 block in registers (v_perm_b32) and writes eight 8-byte pieces to an LDS tile
-// laid out [column][64 rows], so the fragment reads are the forward kernels' 16-byte reads.  LDS
-// rows are 128 bytes; 16-byte chunk c of row m sits at chunk c ^ (((m >> 1) ^ (m >> 3)) & 7), which
-// spreads both access patterns over the banks: fragment reads (32 consecutive rows, two chunks)
-// and transposed writes (rows 8 apart, two adjacent halves).  Two LDS stages: the global loads of
-// step s+1 are in flight during the products of step s and are written to the other stage after
-// them; one barrier per step.  Outputs are f32 (gradient accumulation across calls is exact to f32),
-// stored straight from the accumulators: 32 lanes cover 128 contiguous bytes.
-// A group's tiles are launched on one XCD (workgroup id % 8), so its rows are fetched into one L2.
+// bf16 kernel (namespace wgd below).  Block = 256 threads = 4 waves (2 x 2), block tile 256 x 256
+// outputs, wave tile 128 x 128 = 4 x 4 v_mfma_f32_32x32x16_bf16 tiles (256 accumulator registers, one
+// block per CU).  Outputs are f32 (gradient accumulation across calls is exact to f32), stored
+// straight from the accumulators: 32 lanes cover 128 contiguous bytes.  A group's tiles are
+// launched on one XCD (workgroup id % 8), so its rows are fetched into one L2.
 #include "common.h"
 
 namespace occult {
@@ -45,15 +37,60 @@ struct WgradArgs {
   int accumulate;            // 0: C = product, 1: C += product
 };
 
-namespace wg {
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int OP_BYTES = 256 * 128;   // one operand tile: 256 columns x 64 rows of bf16
-constexpr int STAGE_BYTES = 2 * OP_BYTES;
+// ------------------------------------------------------------------------------------------
+// The MFMA operands want 8 consecutive contracted elements per lane, which in memory are 8
+// different rows.  A first version staged the operands through registers (16-byte loads of 4 rows,
+// a 4 x 8 transpose with v_perm_b32, 8-byte LDS writes): it can keep only one step of operands
+// (64 KiB per CU) in flight, which covers a step's products but not the latency of memory under
+// load (measured: products alone 985 TFLOP/s, with the loads 480).  Here a step is 32 rows, the raw
+// row-major tiles go from global memory straight into a ring of NST LDS stages
+// (global_load_lds_dwordx4: no registers held while a load is in flight), NST - 1 steps ahead, and
+// the transposition happens in the fragment reads: ds_read_b64_tr_b16 gives every lane
+// of a 16-lane block the 4 contracted elements of its own column out of 4 rows x 16 columns that the
+// block's lanes address (lanes 4e..4e+3 address row e).  Two such reads make one MFMA operand.
+// One load instruction fills 1 KiB = 2 tile rows; 16-byte chunk c of tile row k sits at chunk
+// c ^ ((k & 3) << 2) (realised by the loading lane's choice of source chunk), so that the 4 rows x
+// 64 bytes a block reads fall on different banks.  Rows past the group's end: the A side reads a
+// page of zeros, the B side repeats the group's last row (0 * finite = 0).  Gathered row indices
+// take the same road two steps ahead of the rows they address: one 4-byte-per-lane LDS-directed
+// load per wave and step into a small ring, read back with ordinary LDS reads.  Every step issues
+// the same number of loads (steps past the end are clamped like rows past the end), so one
+// constant vmcnt tells that the current step's tiles, and the indices about to be used, have landed.
+namespace wgd {
+constexpr int BM = 256, BN = 256, BK = 32;
+constexpr int NST = 4;   // the index ring below assumes 4
+constexpr int OP_BYTES = BK * 512;          // raw operand tile: 32 rows x 256 columns of bf16
+constexpr int STAGE_BYTES = 2 * OP_BYTES;   // 32 KiB
 
-__device__ __forceinline__ int swz(int m) { return ((m >> 1) ^ (m >> 3)) & 7; }
+__device__ __attribute__((aligned(16))) const unsigned zero_page[4] = {0u, 0u, 0u, 0u};
 
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+// 64 lanes x 16 bytes from per-lane global addresses to LDS [lds, lds + 1024); counted by vmcnt
+__device__ __forceinline__ void load_to_lds_16(const char* src, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(src) : "memory", "m0");
+}
+// the same with a wave-uniform base and a 32-bit byte offset per lane
+__device__ __forceinline__ void load_to_lds_16(const char* base, unsigned off, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(off), "s"(base)
+               : "memory", "m0");
+}
+// 64 lanes x 4 bytes to LDS [lds, lds + 256)
+__device__ __forceinline__ void load_to_lds_4(const char* src, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds), "v"(src) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+#pragma clang diagnostic pop
+
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+template <bool GATHER>   // B rows through a.b_rows
 __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
-  __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char smem[NST * STAGE_BYTES];
+  __shared__ __attribute__((aligned(256))) int s_idx[4][4][64];   // [wave][step % 4][row of the wave's 8, repeated]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
@@ -69,55 +106,10 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
     r0 = a.grp_offset[group];
     r1 = a.grp_offset[group + 1];
   }
+  r0 = __builtin_amdgcn_readfirstlane(r0);
+  r1 = __builtin_amdgcn_readfirstlane(r1);
   const long long widx = a.grp_widx ? a.grp_widx[group] : (a.w_base + group);
   const int nk = (r1 - r0 + BK - 1) / BK;
-
-  // loader role: vector column vm (8 elements), row quad rq of each 32-row half of a step
-  const int vm = tid & 31, rq = tid >> 5;
-  const bool a_ok = m0 + vm * 8 < a.M, b_ok = n0 + vm * 8 < a.N;   // host: M % 8 == 0, N % 8 == 0
-  const char* a_base = static_cast<const char*>(a.A) + (long long)(a.a_col0 + group * a.a_group_cols + m0 + vm * 8) * 2;
-  const char* b_base = static_cast<const char*>(a.B) + (long long)(a.b_col0 + group * a.b_group_cols + n0 + vm * 8) * 2;
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  u32x4 ra[2][4], rb[2][4];
-  auto load = [&](int s) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int r = r0 + s * BK + p * 32 + rq * 4 + i;
-        const bool in = r < r1;   // rows past the group's end contribute zeros
-        ra[p][i] = zero4;
-        rb[p][i] = zero4;
-        if (in && a_ok) ra[p][i] = *reinterpret_cast<const u32x4*>(a_base + (long long)r * a.lda * 2);
-        if (in && b_ok) {
-          const long long src = a.b_rows ? a.b_rows[r] : r;
-          rb[p][i] = *reinterpret_cast<const u32x4*>(b_base + src * a.ldb * 2);
-        }
-      }
-  };
-  // 4 rows x 8 columns in registers -> eight (column, 4 rows) pieces of 8 bytes
-  auto write_op = [&](char* dst, const u32x4 (&v)[2][4]) {
-#pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const int kq = p * 8 + rq;   // which group of 4 rows of the step
-#pragma unroll
-      for (int d = 0; d < 4; ++d)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const unsigned sel = h ? 0x07060302u : 0x05040100u;
-          uint2 piece;
-          piece.x = __builtin_amdgcn_perm(v[p][1][d], v[p][0][d], sel);
-          piece.y = __builtin_amdgcn_perm(v[p][3][d], v[p][2][d], sel);
-          const int col = vm * 8 + d * 2 + h;
-          *reinterpret_cast<uint2*>(dst + col * 128 + (((kq >> 1) ^ swz(col)) * 16) + (kq & 1) * 8) = piece;
-        }
-    }
-  };
-  auto write = [&](int buf) {
-    char* st = smem + buf * STAGE_BYTES;
-    write_op(st, ra);
-    write_op(st + OP_BYTES, rb);
-  };
 
   f32x16 acc[4][4];
 #pragma unroll
@@ -127,42 +119,129 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[mi][ni][e] = 0.0f;
 
-  const int frow = lane & 31, fk = lane >> 5;
-  auto compute = [&](int buf) {
-    const char* As = smem + buf * STAGE_BYTES;
-    const char* Bs = As + OP_BYTES;
+  if (nk > 0) {
+    // loader role: a load instruction covers tile rows kb, kb + 1; lane = (row rr, chunk position p)
+    const int rr = lane >> 5, p = lane & 31;
+    const char* a_cols = static_cast<const char*>(a.A) + (long long)(a.a_col0 + group * a.a_group_cols + m0) * 2;
+    const char* b_cols = static_cast<const char*>(a.B) + (long long)(a.b_col0 + group * a.b_group_cols + n0) * 2;
+    const long long a_pitch = (long long)a.lda * 2, b_pitch = (long long)a.ldb * 2;
+    const int a_chunks = min(32, (a.M - m0) / 8), b_chunks = min(32, (a.N - n0) / 8);   // valid 16-byte chunks per row
+    const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;   // LDS byte address
+    const char* zeros = reinterpret_cast<const char*>(zero_page);
+
+    // per-lane byte offsets of the 4 loads per operand inside a step's 32 rows: constant over the steps
+    unsigned off_a[4], off_b[4], chunk_b[4];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[4], fb[4];
-      const int c = ks * 2 + fk;
+    for (int i = 0; i < 4; ++i) {
+      const int k = wave * 8 + i * 2 + rr;           // tile row of this lane
+      int ca = p ^ ((k & 3) << 2), cb = ca;          // source chunk of this lane's position
+      if (ca >= a_chunks) ca = 0;                     // columns past M or N: any valid chunk (never stored)
+      if (cb >= b_chunks) cb = 0;
+      off_a[i] = (unsigned)(k * a_pitch + ca * 16);
+      off_b[i] = (unsigned)(k * b_pitch + cb * 16);
+      chunk_b[i] = (unsigned)(cb * 16);
+    }
+    auto issue = [&](int s) {   // the 8 loads of this wave for step s into stage s % NST
+      const unsigned st = smem_base + (unsigned)(s % NST) * STAGE_BYTES;
+      const int row0 = r0 + s * BK;                    // first row of the step
+      if (row0 + BK <= r1) {   // block-uniform: every row inside the group, addresses = uniform base + constant offsets
+        const char* a_step = a_cols + (long long)row0 * a_pitch;
+        const char* b_step = b_cols + (long long)row0 * b_pitch;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned kb = (unsigned)(wave * 8 + i * 2);
+          load_to_lds_16(a_step, off_a[i], st + kb * 512u);
+          if (GATHER) {
+            const long long rb = s_idx[wave][s & 3][i * 2 + rr];   // fetched two steps ago
+            load_to_lds_16(b_cols + rb * b_pitch + chunk_b[i], st + (unsigned)OP_BYTES + kb * 512u);
+          } else {
+            load_to_lds_16(b_step, off_b[i], st + (unsigned)OP_BYTES + kb * 512u);
+          }
+        }
+      } else {                 // the group's last rows, and the steps past them that keep the load count constant
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int kb = wave * 8 + i * 2;               // tile rows kb, kb + 1
+          const long long ra = row0 + kb + rr;
+          // A: rows past the end read zeros
+          const char* src_a = (ra < r1) ? a_cols + ra * a_pitch + (off_a[i] - (unsigned)((kb + rr) * a_pitch)) : zeros;
+          load_to_lds_16(src_a, st + (unsigned)kb * 512u);
+          // B: rows past the end repeat the last row (the fetched indices are clamped the same way)
+          long long rb = min(row0 + kb + rr, r1 - 1);
+          if (GATHER) rb = s_idx[wave][s & 3][i * 2 + rr];
+          load_to_lds_16(b_cols + rb * b_pitch + chunk_b[i], st + (unsigned)OP_BYTES + (unsigned)kb * 512u);
+        }
+      }
+    };
+
+    // fragment reads: lane l = 16 b + j, j = 4 e + q: block b covers columns 16 (b & 1) .. + 16 and rows
+    // 8 (b >> 1) + e (first read), + 4 (second read); the lane addresses 4 columns (8 bytes) of row e
+    const int fb = lane >> 4, fe = (lane >> 2) & 3, fq = lane & 3;
+    const int f_row = 8 * (fb >> 1) + fe;                       // + 16 * ks, + 4 for the second read
+    const int f_col4 = 4 * (fb & 1) + fq;                       // 8-byte unit inside the 32-column block
+    typedef __attribute__((address_space(3))) char lds_char;
+    auto frag = [&](const lds_char* op, int col0, int ks) -> bf16x8 {   // col0: first column of the 32-column block
+      const int row = ks * 16 + f_row;
+      const int unit = (col0 >> 2) + f_col4;                    // 8-byte unit inside the tile row
+      const int pos = ((unit >> 1) ^ (fe << 2)) * 16 + (unit & 1) * 8;
+      const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+          (bf16x4 __attribute__((address_space(3)))*)(op + row * 512 + pos));
+      const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+          (bf16x4 __attribute__((address_space(3)))*)(op + (row + 4) * 512 + pos));
+      return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    auto read_frags = [&](int s, int ks, bf16x8 (&fa)[4], bf16x8 (&fbv)[4]) {
+      const lds_char* As = (const lds_char*)smem + (s % NST) * STAGE_BYTES;
+      const lds_char* Bs = As + OP_BYTES;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int ml = wm * 128 + i * 32 + frow, nl = wn * 128 + i * 32 + frow;
-        fa[i] = *reinterpret_cast<const bf16x8*>(As + ml * 128 + ((c ^ swz(ml)) * 16));
-        fb[i] = *reinterpret_cast<const bf16x8*>(Bs + nl * 128 + ((c ^ swz(nl)) * 16));
+        fa[i] = frag(As, wm * 128 + i * 32, ks);
+        fbv[i] = frag(Bs, wn * 128 + i * 32, ks);
       }
+    };
+    auto mma = [&](const bf16x8 (&fa)[4], const bf16x8 (&fbv)[4]) {
 #pragma unroll
       for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 4; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
-    }
-  };
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fbv[ni], acc[mi][ni], 0, 0, 0);
+    };
 
-  if (nk > 0) {
-    load(0);
-    write(0);
-  }
-  __syncthreads();
-  for (int s = 0; s < nk; ++s) {
-    const bool more = s + 1 < nk;   // block-uniform
-    if (more) load(s + 1);
-    compute(s & 1);
-    if (more) write((s + 1) & 1);
-    __syncthreads();
+    // source rows of this wave's 8 tile rows of step s (clamped to the group) -> its ring slot s % 4
+    const unsigned idx_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)&s_idx[wave][0][0];
+    auto issue_idx = [&](int s) {
+      const int r = min(r0 + s * BK + wave * 8 + (lane & 7), r1 - 1);
+      load_to_lds_4(reinterpret_cast<const char*>(a.b_rows + r), idx_base + (unsigned)(s & 3) * 256u);
+    };
+    constexpr int OPS = GATHER ? 9 : 8;   // loads per wave and step
+    if (GATHER) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) issue_idx(s);          // one ring of indices
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a wave reads only its own indices: no barrier
+    }
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s);
+    if (GATHER) issue_idx(NST);                          // into the slot step 0 has just been read from
+    for (int s = 0; s < nk; ++s) {
+      // Loads complete in order.  Per step a wave issues [indices of step s + NST + 1,] 8 tile loads of step
+      // s + NST - 1.  The tiles of step s are older than the (NST - 2) * OPS loads of the last NST - 2 steps;
+      // the indices used below (step s + NST - 1, issued first two steps ago) are older than all but one of them.
+      wait_loads_and_barrier<(NST - 2) * OPS - (GATHER ? 1 : 0)>();
+      // after the barrier every wave's tiles of step s are in LDS, and every wave is done with the stage that
+      // step s + NST - 1 overwrites
+      bf16x8 fa[2][4], fbv[2][4];
+      read_frags(s, 0, fa[0], fbv[0]);
+      if (GATHER) issue_idx(s + NST + 1);
+      issue(s + NST - 1);      // address arithmetic and issue run while the first fragments arrive
+      read_frags(s, 1, fa[1], fbv[1]);
+      mma(fa[0], fbv[0]);
+      mma(fa[1], fbv[1]);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the clamped loads past the end, before the block's LDS is released
   }
 
   // accumulator element e of lane l: output row (e / 4) * 8 + (l / 32) * 4 + e % 4, column l % 32 of its 32 x 32 tile
+  const int frow = lane & 31, fk = lane >> 5;
   float* cmat = a.C + widx * a.c_mat_stride;
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
@@ -181,7 +260,7 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
       }
     }
 }
-}  // namespace wg
+}  // namespace wgd
 
 // f32 path for parity-sized layers: one thread per output element, rows summed in order
 __global__ __launch_bounds__(256) void wgrad_f32(const WgradArgs a) {
@@ -208,10 +287,11 @@ __global__ __launch_bounds__(256) void wgrad_f32(const WgradArgs a) {
 static int launch_wgrad(const occult_cfg_t& c, const WgradArgs& a, hipStream_t s) {
   if (a.ngroups == 0 || a.M == 0 || a.N == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
-    const long long tiles = (long long)((a.M + wg::BM - 1) / wg::BM) * ((a.N + wg::BN - 1) / wg::BN);
+    const long long tiles = (long long)((a.M + wgd::BM - 1) / wgd::BM) * ((a.N + wgd::BN - 1) / wgd::BN);
     const long long blocks = (long long)((a.ngroups + 7) / 8) * tiles * 8;
     OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "weight-gradient grid too large");
-    hipLaunchKernelGGL(wg::wgrad_bf16, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    if (a.b_rows) hipLaunchKernelGGL(wgd::wgrad_bf16<true>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(wgd::wgrad_bf16<false>, dim3((unsigned)blocks), dim3(256), 0, s, a);
   } else {
     OCC_REQUIRE(a.ngroups <= 65535, OCCULT_EINVAL, "too many groups");
     hipLaunchKernelGGL(wgrad_f32, dim3((a.N + 15) / 16, (a.M + 15) / 16, a.ngroups), dim3(256), 0, s, a);
