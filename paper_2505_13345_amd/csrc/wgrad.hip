@@ -12,8 +12,8 @@
 // bf16 kernel (namespace wgd below).  Block = 256 threads = 4 waves (2 x 2), block tile 256 x 256
 // outputs, wave tile 128 x 128 = 4 x 4 v_mfma_f32_32x32x16_bf16 tiles (256 accumulator registers, one
 // block per CU).  Outputs are f32 (gradient accumulation across calls is exact to f32), stored
-// straight from the accumulators: 32 lanes cover 128 contiguous bytes.  A group's tiles are
-// launched on one XCD (workgroup id % 8), so its rows are fetched into one L2.
+// straight from the accumulators: 32 lanes cover 128 contiguous bytes.  With 8 groups or more a
+// group's tiles are launched on one XCD (workgroup id % 8), so its rows are fetched into one L2.
 #include "common.h"
 
 namespace occult {
@@ -96,10 +96,18 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
   const int wm = wave >> 1, wn = wave & 1;
   const int nt_n = (a.N + BN - 1) / BN;
   const int tiles = ((a.M + BM - 1) / BM) * nt_n;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int group = (slot / tiles) * 8 + xcd;
+  // with 8 groups or more a group's tiles share an XCD (and its L2); fewer groups (shared experts: few
+  // groups of many rows) are spread over all XCDs instead
+  int group, tile;
+  if (a.ngroups >= 8) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    group = (slot / tiles) * 8 + xcd;
+    tile = slot % tiles;
+  } else {
+    group = blockIdx.x / tiles;
+    tile = blockIdx.x % tiles;
+  }
   if (group >= a.ngroups) return;   // whole block; before any barrier
-  const int tile = slot % tiles;
   const int m0 = (tile / nt_n) * BM, n0 = (tile % nt_n) * BN;
   int r0 = 0, r1 = a.R;
   if (a.grp_offset) {
@@ -288,7 +296,7 @@ static int launch_wgrad(const occult_cfg_t& c, const WgradArgs& a, hipStream_t s
   if (a.ngroups == 0 || a.M == 0 || a.N == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
     const long long tiles = (long long)((a.M + wgd::BM - 1) / wgd::BM) * ((a.N + wgd::BN - 1) / wgd::BN);
-    const long long blocks = (long long)((a.ngroups + 7) / 8) * tiles * 8;
+    const long long blocks = a.ngroups >= 8 ? (long long)((a.ngroups + 7) / 8) * tiles * 8 : (long long)a.ngroups * tiles;
     OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "weight-gradient grid too large");
     if (a.b_rows) hipLaunchKernelGGL(wgd::wgrad_bf16<true>, dim3((unsigned)blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(wgd::wgrad_bf16<false>, dim3((unsigned)blocks), dim3(256), 0, s, a);
