@@ -1,7 +1,7 @@
 /*
  * occult.h - C ABI of the MI355X (gfx950) library for the hot path of a collaboration-aware
- * expert-parallel mixture-of-experts layer (Occult, arXiv 2505.13345): the forward pass, and the
- * backward pass of its data movement and routing weights.
+ * expert-parallel mixture-of-experts layer (Occult, arXiv 2505.13345): the forward pass and the
+ * backward pass (data movement, experts' input and weight gradients, routing weights).
  *
  * One GPU's share of the layer: the D devices of expert parallelism are simulated as
  * groups of G = E / D experts on one GPU, the rows they would exchange are packed into
