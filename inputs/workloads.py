@@ -54,7 +54,7 @@ class LayerShape:
         return self.E // self.D
 
 
-# The five configurations of the build's baseline file, in its order.
+# The five benchmark configurations.
 CONFIGS = {
     "tiny_f32": LayerShape("tiny_f32", T=256, d=128, f=256, E=16, S=0, k=4, D=4,
                            dtype="f32", components=0),

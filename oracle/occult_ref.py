@@ -12,7 +12,7 @@ Followed passages (paper, Section 3.1 and Appendix A):
     "Weight Modulation", "SMM with Merging", "Combine" (Appendix A.2);
   * replica count C_T = N_sfd / N_ori and its bounds (Section 2.2).
 
-Readings (each also listed in the design notes):
+Readings:
   * one source rank is simulated: segment d of the send buffer *is* what device d
     receives, and the return trip is the identity;
   * the BRIM_0 counter runs over all devices (device-major, token-ascending), so its

@@ -14,7 +14,7 @@ Collaboration Pruning", routing-score-based variant):
 * with pruning (n_d > 0) each token may use experts of at most n_d devices.
   The surviving devices are chosen either
     mode 1: by the summed gate score of the token's unpruned top-k experts per
-            device (highest n_d sums; the build's baseline file fixes this rule), or
+            device (highest n_d sums; the rule of this build's benchmark configurations), or
     mode 2: by walking the unpruned top-k in descending score order and keeping
             the first n_d distinct devices met (the paper's wording);
   then the k highest-scoring experts *on the surviving devices* are selected

@@ -1,7 +1,7 @@
 """GPU parity for occult_expert_ffn and the whole hot path (route -> plan -> dispatch -> expert
 FFN -> combine) against the textbook layer O-std in float64.
 
-Bars (from the build's baseline file): f32 outputs within max-rel 1e-5 (relative to
+Bars: f32 outputs within max-rel 1e-5 (relative to
 max(|o|, rms(o)) so that entries near zero do not dominate), bf16 outputs within max-abs 2e-2
 and mean-abs 2e-3 of the oracle's exactly accumulated result.
 """
