@@ -215,6 +215,28 @@ int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, con
                          void* h_shared, void* y_shared, void* ws, size_t ws_bytes,
                          occult_stream_t stream);
 
+/* Optional repacked weights for decode-shaped batches (paper Sec. 4, decoding: few rows per expert, the
+ * expert computation is streaming every active expert's weights once).  Below 24 rows per expert
+ * on average the bf16 products run a kernel in which a wave streams its 32 output columns' weights;
+ * in the layout of occult_weights_t that is 32 or 64 rows 4 KiB apart, 128 bytes at a time.
+ * occult_pack_weights writes the same numbers once (again after every weight update) in the order
+ * that kernel reads them, one contiguous stream per wave: `packed` is a device ptr of
+ * occult_pack_weights_bytes() bytes (3*(E+S)*d*f elements; 0 for f32, where the call does nothing),
+ * 16-byte aligned.  Layout: all gate|up pairs, then all down matrices; per pair, units of 32 output
+ * columns; per unit, stages of 64 K elements = 8 blocks of 1 KiB ordered (K step of 32, gate or up,
+ * column block of 16); a block is 64 pieces of 16 bytes, piece l = row l%16 of the column block at K
+ * offset (l/16)*8; the down matrices likewise with 4 blocks per stage.
+ * occult_expert_ffn_packed is occult_expert_ffn_ws reading `packed` wherever that kernel is chosen
+ * and `weights` elsewhere (both must hold the same numbers); results are bit-identical to
+ * occult_expert_ffn_ws.  packed == NULL: the same call. */
+int occult_pack_weights_bytes(const occult_cfg_t* cfg, size_t* bytes);
+int occult_pack_weights(const occult_cfg_t* cfg, const occult_weights_t* weights, void* packed,
+                        size_t packed_size, occult_stream_t stream);
+int occult_expert_ffn_packed(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                             const void* x, const occult_weights_t* weights, const void* packed,
+                             void* epd_h, void* epd_y, void* h_shared, void* y_shared, void* ws,
+                             size_t ws_bytes, occult_stream_t stream);
+
 /* Two-stage combine (paper Sec. 3.1 two-stage aggregation of Eq. 0; App. A.2 "Weight
  * Modulation", the accumulation of "SMM with Merging", and "Combine").
  * Stage 1 (on the device, before the return trip): sfd_y[r] = sum over the EPD rows q of SFD

@@ -25,6 +25,7 @@ EXPORTS = [
     "occult_similarity_gram", "occult_similarity_table", "occult_expert_ffn_ws_bytes", "occult_expert_ffn_ws",
     "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
     "occult_transpose_weights", "occult_expert_ffn_backward", "occult_expert_ffn_backward_weights",
+    "occult_pack_weights_bytes", "occult_pack_weights", "occult_expert_ffn_packed",
 ]
 
 
@@ -90,6 +91,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_expert_ffn_ws_bytes.argtypes = [cfgp, POINTER(c_size_t)]
     lib.occult_expert_ffn_ws.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t),
                                          c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.occult_pack_weights_bytes.argtypes = [cfgp, POINTER(c_size_t)]
+    lib.occult_pack_weights.argtypes = [cfgp, POINTER(occult_weights_t), c_void_p, c_size_t, c_void_p]
+    lib.occult_expert_ffn_packed.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t), c_void_p,
+                                             c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.occult_combine.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_combine_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                             c_void_p]
@@ -216,6 +221,27 @@ def occult_expert_ffn_ws(cfg, plan, sfd_x, x, w_gate, w_up, w_down, epd_h, epd_y
     _check(load_library().occult_expert_ffn_ws(ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x),
                                                ctypes.byref(wts), _ptr(epd_h), _ptr(epd_y), _ptr(h_shared),
                                                _ptr(y_shared), _ptr(ws), nbytes, _stream(stream)))
+
+
+def occult_pack_weights_bytes(cfg) -> int:
+    n = c_size_t(0)
+    _check(load_library().occult_pack_weights_bytes(ctypes.byref(cfg), ctypes.byref(n)))
+    return int(n.value)
+
+
+def occult_pack_weights(cfg, w_gate, w_up, w_down, packed, stream=None) -> None:
+    wts = occult_weights_t(_ptr(w_gate), _ptr(w_up), _ptr(w_down))
+    _check(load_library().occult_pack_weights(ctypes.byref(cfg), ctypes.byref(wts), _ptr(packed),
+                                              packed.numel() * packed.element_size(), _stream(stream)))
+
+
+def occult_expert_ffn_packed(cfg, plan, sfd_x, x, w_gate, w_up, w_down, packed, epd_h, epd_y, h_shared, y_shared, ws,
+                             stream=None) -> None:
+    wts = occult_weights_t(_ptr(w_gate), _ptr(w_up), _ptr(w_down))
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().occult_expert_ffn_packed(ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x),
+                                                   ctypes.byref(wts), _ptr(packed), _ptr(epd_h), _ptr(epd_y),
+                                                   _ptr(h_shared), _ptr(y_shared), _ptr(ws), nbytes, _stream(stream)))
 
 
 def occult_combine(cfg, plan, epd_y, sfd_y, y_shared, y, stream=None) -> None:

@@ -269,11 +269,12 @@ namespace skinny {
 constexpr int BN_OUT = 32;
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-template <bool SWIGLU, int MT>   // MT token blocks of 16 per m-tile
+template <bool SWIGLU, int MT, bool PACKED>   // MT token blocks of 16 per m-tile; PACKED: weights from a.Bp
 __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   constexpr int BM = 16 * MT;
   constexpr int KS = MT <= 2 ? 2 : 1;   // 32-wide K steps per pipeline stage
   constexpr int NW = SWIGLU ? 2 : 1;
+  static_assert(!PACKED || KS == 2, "the packed order is written for two K steps per stage");
   __shared__ TileInfo s_info;
   const int n_cb = a.N / BN_OUT;   // column blocks (host: N % 32 == 0)
   const int wgs_per_mt = (n_cb + 3) / 4;
@@ -296,6 +297,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     for (int nb = 0; nb < 2; ++nb)
       w[m][nb] = static_cast<const char*>(m == 0 ? a.B : a.B2) +
                  ((widx * a.b_group_stride + (long long)(n0 + nb * 16 + r) * a.ldb) * 2 + c * 16);
+  // packed order: this wave's unit is one contiguous stream of stages, a load instruction reads 1 KiB of it
+  const char* wp = PACKED ? static_cast<const char*>(a.Bp) + widx * a.bp_group_stride +
+                                (long long)cb * (BN_OUT * NW * 2) * a.K + lane * 16
+                          : nullptr;
   const char* xa[MT];
 #pragma unroll
   for (int tb = 0; tb < MT; ++tb) {
@@ -338,7 +343,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
         for (int nb = 0; nb < 2; ++nb)
           {
             // measured: the streaming hint helps the single-matrix product and hurts the gate/up pair
-            const bf16x8* src = reinterpret_cast<const bf16x8*>(w[m][nb] + woff + ks * 64);
+            const bf16x8* src = PACKED ? reinterpret_cast<const bf16x8*>(wp + (long long)i * (KS * NW * 2048) +
+                                                                           ((ks * NW + m) * 2 + nb) * 1024)
+                                       : reinterpret_cast<const bf16x8*>(w[m][nb] + woff + ks * 64);
             st.wf[ks][m][nb] = SWIGLU ? *src : __builtin_nontemporal_load(src);
           }
 #pragma unroll
@@ -957,6 +964,39 @@ static int choose_ksplit(long long tiles, int nk) {
   return ks >= 2 ? (int)ks : 0;
 }
 
+// Weights in the weight-streaming kernel's own order (bf16).  Region 1, gate and up, per weight
+// matrix pair 4*f*d bytes: unit = 32 output columns, stage = 64 K elements; a stage is 8 blocks of
+// 1 KiB in the order (K step ks, matrix m: gate or up, column block nb), block = 64 lanes x 16 bytes,
+// lane l holding row nb*16 + l%16 of the unit at K offset ks*32 + (l/16)*8.  Region 2, down, per
+// matrix 2*d*f bytes: the same with one matrix (4 blocks per stage).  One thread per 16-byte piece.
+__global__ __launch_bounds__(256) void pack_weights_kernel(const u32x4* __restrict__ gate, const u32x4* __restrict__ up,
+                                                           const u32x4* __restrict__ down, u32x4* __restrict__ out,
+                                                           int n_mats, int d, int f) {
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long per1 = (long long)f * d / 4, per2 = (long long)d * f / 8;   // pieces per matrix pair / matrix
+  const long long n1 = n_mats * per1;
+  if (idx < n1) {
+    const int e = (int)(idx / per1);
+    long long rem = idx - e * per1;
+    const int cb = (int)(rem / (8ll * d));           // unit: 32 columns x 2 matrices x d elements
+    rem -= cb * 8ll * d;
+    const int stage = (int)(rem / 512), blk = (int)(rem % 512) / 64, lane = (int)(rem % 64);
+    const int ks = blk >> 2, m = (blk >> 1) & 1, nb = blk & 1;
+    const int n = cb * 32 + nb * 16 + (lane & 15), k = stage * 64 + ks * 32 + (lane >> 4) * 8;
+    out[idx] = (m ? up : gate)[(((long long)e * f + n) * d + k) / 8];
+  } else if (idx < n1 + n_mats * per2) {
+    const long long i2 = idx - n1;
+    const int e = (int)(i2 / per2);
+    long long rem = i2 - e * per2;
+    const int cb = (int)(rem / (4ll * f));           // unit: 32 columns x f elements
+    rem -= cb * 4ll * f;
+    const int stage = (int)(rem / 256), blk = (int)(rem % 256) / 64, lane = (int)(rem % 64);
+    const int ks = blk >> 1, nb = blk & 1;
+    const int n = cb * 32 + nb * 16 + (lane & 15), k = stage * 64 + ks * 32 + (lane >> 4) * 8;
+    out[idx] = down[(((long long)e * d + n) * f + k) / 8];
+  }
+}
+
 int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
   if (total_rows == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
@@ -976,8 +1016,11 @@ int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total
       const long long blocks = m_tiles * ((a.N / skinny::BN_OUT + 3) / 4);
       OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
       const dim3 grid((unsigned)blocks), block(256);
-      if (swiglu) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2>), grid, block, 0, s, a);
-      else hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2>), grid, block, 0, s, a);
+      const bool packed = a.Bp != nullptr && a.kseg == a.K;   // the packed order holds one matrix along K
+      if (swiglu && packed) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2, true>), grid, block, 0, s, a);
+      else if (swiglu) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2, false>), grid, block, 0, s, a);
+      else if (packed) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2, true>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2, false>), grid, block, 0, s, a);
       OCC_LAUNCH_CHECK("grouped_gemm");
       return OCCULT_OK;
     }
@@ -1058,8 +1101,9 @@ extern "C" int occult_expert_ffn_ws_bytes(const occult_cfg_t* cfg, size_t* ws_by
 }
 
 static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
-                           const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
-                           void* h_shared, void* y_shared, void* ws, size_t ws_bytes, occult_stream_t stream) {
+                           const void* x, const occult_weights_t* weights, const void* packed, void* epd_h,
+                           void* epd_y, void* h_shared, void* y_shared, void* ws, size_t ws_bytes,
+                           occult_stream_t stream) {
   int rc = check_cfg(cfg);
   if (rc) return rc;
   const occult_cfg_t c = *cfg;
@@ -1125,6 +1169,7 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
       g1.A = sfd_x; g1.lda = c.d; g1.a_rows = plan->epd_sfd_row;
       g1.B = weights->w_gate; g1.B2 = weights->w_up;
       g1.b_group_stride = (long long)c.f * c.d; g1.ldb = c.d; g1.kseg = c.d;
+      g1.Bp = packed; g1.bp_group_stride = 4ll * c.f * c.d;
       g1.C = epd_h; g1.ldc = c.f; g1.c_col0 = 0;
       g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.w_base = 0;
       g1.ngroups = c.E; g1.M = 0; g1.N = c.f; g1.K = c.d;
@@ -1137,6 +1182,8 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
       g2.A = epd_h; g2.lda = c.f; g2.a_rows = nullptr;
       g2.B = weights->w_down; g2.B2 = nullptr;
       g2.b_group_stride = (long long)c.d * c.f; g2.ldb = c.f; g2.kseg = c.f;
+      if (packed) g2.Bp = static_cast<const char*>(packed) + 4ll * c.f * c.d * (c.E + c.S);
+      g2.bp_group_stride = 2ll * c.d * c.f;
       g2.C = epd_y; g2.ldc = c.d; g2.c_col0 = 0;
       g2.grp_offset = plan->exp_offset; g2.grp_widx = plan->pos_expert; g2.w_base = 0;
       g2.ngroups = c.E; g2.M = 0; g2.N = c.d; g2.K = c.f;
@@ -1158,7 +1205,7 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
 extern "C" int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
                                  const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
                                  void* h_shared, void* y_shared, occult_stream_t stream) {
-  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, epd_h, epd_y, h_shared, y_shared, nullptr, 0, stream);
+  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, nullptr, epd_h, epd_y, h_shared, y_shared, nullptr, 0, stream);
 }
 
 extern "C" int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
@@ -1166,5 +1213,51 @@ extern "C" int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t
                                     void* h_shared, void* y_shared, void* ws, size_t ws_bytes,
                                     occult_stream_t stream) {
   if (ws != nullptr) OCC_REQUIRE(aligned16(ws), OCCULT_EALIGN, "ws is not 16-byte aligned");
-  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, epd_h, epd_y, h_shared, y_shared, ws, ws_bytes, stream);
+  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, nullptr, epd_h, epd_y, h_shared, y_shared, ws, ws_bytes, stream);
+}
+
+static size_t packed_bytes(const occult_cfg_t& c) {
+  return c.dtype == OCCULT_BF16 ? (size_t)(c.E + c.S) * 3 * c.d * c.f * 2 : 0;
+}
+
+extern "C" int occult_pack_weights_bytes(const occult_cfg_t* cfg, size_t* bytes) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  OCC_REQUIRE(bytes, OCCULT_ENULLPTR, "bytes is NULL");
+  *bytes = packed_bytes(*cfg);
+  return OCCULT_OK;
+}
+
+extern "C" int occult_pack_weights(const occult_cfg_t* cfg, const occult_weights_t* weights, void* packed,
+                                   size_t packed_size, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  if (c.dtype != OCCULT_BF16) return OCCULT_OK;   // the f32 path has no weight-streaming kernel
+  OCC_REQUIRE(weights && weights->w_gate && weights->w_up && weights->w_down && packed, OCCULT_ENULLPTR,
+              "weights, one of its tensors or packed is NULL");
+  OCC_REQUIRE(c.d % 64 == 0 && c.f % 64 == 0, OCCULT_ESHAPE,
+              "bf16 path needs d and f to be multiples of 64 (d=%d, f=%d)", c.d, c.f);
+  OCC_REQUIRE(packed_size >= packed_bytes(c), OCCULT_EWORKSPACE, "packed buffer of %zu bytes < required %zu", packed_size,
+              packed_bytes(c));
+  OCC_REQUIRE(aligned16(weights->w_gate) && aligned16(weights->w_up) && aligned16(weights->w_down) && aligned16(packed),
+              OCCULT_EALIGN, "a buffer is not 16-byte aligned");
+  const long long pieces = (long long)packed_bytes(c) / 16;
+  OCC_REQUIRE((pieces + 255) / 256 < (1ll << 31), OCCULT_EINVAL, "too many weights for one launch");
+  hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const u32x4*>(weights->w_gate),
+                     static_cast<const u32x4*>(weights->w_up), static_cast<const u32x4*>(weights->w_down),
+                     static_cast<u32x4*>(packed), c.E + c.S, c.d, c.f);
+  OCC_LAUNCH_CHECK("pack_weights_kernel");
+  return OCCULT_OK;
+}
+
+extern "C" int occult_expert_ffn_packed(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                        const void* x, const occult_weights_t* weights, const void* packed,
+                                        void* epd_h, void* epd_y, void* h_shared, void* y_shared, void* ws,
+                                        size_t ws_bytes, occult_stream_t stream) {
+  if (ws != nullptr) OCC_REQUIRE(aligned16(ws), OCCULT_EALIGN, "ws is not 16-byte aligned");
+  if (packed != nullptr) OCC_REQUIRE(aligned16(packed), OCCULT_EALIGN, "packed is not 16-byte aligned");
+  const void* use = (cfg && cfg->dtype == OCCULT_BF16) ? packed : nullptr;
+  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, use, epd_h, epd_y, h_shared, y_shared, ws, ws_bytes, stream);
 }

@@ -11,6 +11,9 @@ struct GemmArgs {
   const int32_t* a_rows;    // [rows] source row of each logical row, or NULL (identity)
   const void* B;            // weights [group][N][kseg]
   const void* B2;           // second weight matrix (up projection) when SWIGLU, same layout
+  const void* Bp;           // the same weights in the weight-streaming kernel's own order (occult_pack_weights),
+                            // or NULL; read instead of B / B2 when that kernel is chosen
+  long long bp_group_stride;   // bytes between consecutive weight matrices (pairs, when SWIGLU) in Bp
   long long b_group_stride; // elements between consecutive weight matrices
   int ldb;                  // elements between B rows (= kseg)
   int kseg;                 // K elements held by one weight matrix; K > kseg walks consecutive matrices

@@ -65,7 +65,22 @@ class OccultLayer:
     def dispatch(self, x):
         B.occult_dispatch(self.cfg, self.plan, x, self.sfd_x)
 
+    def pack_weights(self, w_gate, w_up, w_down):
+        """One-time repacking of the weights for decode-shaped batches (again after a weight update);
+        expert_ffn() then reads the packed copy wherever the weight-streaming kernel runs."""
+        n = B.occult_pack_weights_bytes(self.cfg)
+        if n == 0:
+            return None
+        if getattr(self, "packed", None) is None:
+            self.packed = torch.empty(n // 2, dtype=torch.bfloat16, device=self.device)
+        B.occult_pack_weights(self.cfg, w_gate, w_up, w_down, self.packed)
+        return self.packed
+
     def expert_ffn(self, x, w_gate, w_up, w_down, use_ws=True):
+        if getattr(self, "packed", None) is not None:
+            B.occult_expert_ffn_packed(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.packed, self.epd_h,
+                                       self.epd_y, self.h_shared, self.y_shared, self.ffn_ws if use_ws else None)
+            return
         if use_ws and self.ffn_ws is not None:
             B.occult_expert_ffn_ws(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h,
                                    self.epd_y, self.h_shared, self.y_shared, self.ffn_ws)

@@ -223,3 +223,72 @@ def test_empty_batch_runs_every_call():
     torch.cuda.synchronize()
     assert float(gram.abs().max()) == 0.0 and int(C.abs().max()) == 0
     assert layer.stats().n_sfd == 0
+
+
+def _packed_reference(wg, wu, wd):
+    """The documented packed order written out with numpy (uint16 views of bf16 weights):
+    all gate|up pairs, then all down matrices; units of 32 output columns; stages of 64 K elements;
+    blocks of 1 KiB ordered (K step of 32, gate or up, column block of 16); piece l of a block = row
+    l % 16 of the column block at K offset (l // 16) * 8."""
+    n, f, d = wg.shape
+    lanes = np.arange(64)
+    rows, koff = lanes % 16, (lanes // 16) * 8
+
+    def blocks(mats, N, K):          # mats: list of [N, K] arrays that alternate inside a stage
+        out = []
+        for cb in range(N // 32):
+            for stage in range(K // 64):
+                for ks in range(2):
+                    for m in mats:
+                        for nb in range(2):
+                            r = cb * 32 + nb * 16 + rows
+                            k0 = stage * 64 + ks * 32 + koff
+                            out.append(np.stack([m[r[i], k0[i]:k0[i] + 8] for i in range(64)]).reshape(-1))
+        return np.concatenate(out)
+
+    part1 = [blocks([wg[e], wu[e]], f, d) for e in range(n)]
+    part2 = [blocks([wd[e]], d, f) for e in range(n)]
+    return np.concatenate(part1 + part2)
+
+
+def test_pack_weights_layout_bit_exact():
+    from paper_2505_13345_amd import binding as B
+    dev = require_gpu()
+    E, S, d, f = 3, 1, 128, 64
+    rng = np.random.default_rng(4)
+    layer = OccultLayer(8, d, f, E + 1, S, 2, 2, "bf16")          # E + 1 = 4 routed experts, one shared
+    n = E + 1 + S
+    as_u16 = lambda shape: rng.integers(0, 65536, size=shape, dtype=np.uint16)
+    wg, wu, wd = as_u16((n, f, d)), as_u16((n, f, d)), as_u16((n, d, f))
+    to_bf = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    packed = layer.pack_weights(to_bf(wg), to_bf(wu), to_bf(wd))
+    torch.cuda.synchronize()
+    assert packed.numel() * 2 == B.occult_pack_weights_bytes(layer.cfg) == n * 3 * d * f * 2
+    got = packed.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, _packed_reference(wg, wu, wd))
+    # a buffer that is too small is refused
+    with pytest.raises(B.OccultError) as e:
+        B.occult_pack_weights(layer.cfg, to_bf(wg), to_bf(wu), to_bf(wd), packed[:-8])
+    assert e.value.code == -5
+
+
+@pytest.mark.parametrize("name", ["decode_bf16", "few_rows"])
+def test_packed_weights_give_bit_identical_ffn(name):
+    say(f"packed weights {name}")
+    dev = require_gpu()
+    if name == "decode_bf16":
+        shape = wl.CONFIGS[name]
+    else:   # ragged: some experts empty, some over 32 rows (two row tiles), shared experts on the other kernels
+        shape = wl.LayerShape(name, T=80, d=256, f=192, E=16, S=2, k=4, D=4, dtype="bf16", components=4)
+    wk = wl.make_workload(shape, seed=17)
+    layer, y_plain = _run_layer(shape, wk)
+    epd_h, epd_y = layer.epd_h.clone(), layer.epd_y.clone()
+    x = to_dev(wk.x, shape.dtype, dev)
+    wg, wu, wd = (to_dev(a, shape.dtype, dev) for a in (wk.w_gate, wk.w_up, wk.w_down))
+    layer.pack_weights(wg, wu, wd)
+    layer.epd_h.zero_()
+    layer.epd_y.zero_()
+    y_packed = layer.forward(torch.from_numpy(wk.logits).to(dev), x, wg, wu, wd)
+    torch.cuda.synchronize()
+    assert torch.equal(layer.epd_h, epd_h) and torch.equal(layer.epd_y, epd_y)
+    assert np.array_equal(y_packed.float().cpu().numpy(), y_plain)
