@@ -34,8 +34,8 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0).  prefill: the gate/up GEMM; decode: the five
 # kernels of occult_expert_ffn together (its roofline is on all weight bytes).  Absent = not measured.
 MEASURED_TRAFFIC = {
-    "prefill_bf16": (1060460 * 2.0 + 262144) * 1024,
-    "decode_bf16": ((355433 + 190349 + 24685 + 17042 + 4113) * 2.0 + (1427 + 2049 + 1408 + 8192 + 512)) * 1024,
+    "prefill_bf16": (1062550 * 2.0 + 262144) * 1024,
+    "decode_bf16": ((328353 + 169865 + 24694 + 17041 + 4113) * 2.0 + (1418 + 2048 + 1408 + 8192 + 512)) * 1024,
 }
 
 
