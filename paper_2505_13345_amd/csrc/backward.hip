@@ -63,44 +63,47 @@ __global__ __launch_bounds__(kBwdWaves * 64) void combine_bwd_kernel(
       }
       if (my_q >= 0) my_g = epd_gate[my_q];
     }
-    float g_row[VPL][NE];
-#pragma unroll
-    for (int i = 0; i < VPL; ++i) {
-      const int c = lane + 64 * i;
-      if (c < row_vecs) {
-        R::load(dy, (size_t)t, row_vecs, c, g_row[i]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < NE; ++e) g_row[i][e] = 0.0f;
-      }
-    }
     float my_dw = 0.0f;
-    for (int s = 0; s < k; ++s) {
-      const int q = __builtin_amdgcn_readlane(my_q, s);
-      if (q < 0) continue;   // a plan that does not belong to these ids: nothing to address
-      const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_g), s));
-      float dot = 0.0f;
+    // rows longer than 64 * VPL vectors are done in column chunks; the slot lookup stays in registers
+    for (int cbase = 0; cbase < row_vecs; cbase += 64 * VPL) {
+      float g_row[VPL][NE];
 #pragma unroll
       for (int i = 0; i < VPL; ++i) {
-        const int c = lane + 64 * i;
+        const int c = cbase + lane + 64 * i;
         if (c < row_vecs) {
-          if (dw) {
-            float v[NE];
-            R::load(epd_y, (size_t)q, row_vecs, c, v);
+          R::load(dy, (size_t)t, row_vecs, c, g_row[i]);
+        } else {
 #pragma unroll
-            for (int e = 0; e < NE; ++e) dot = fmaf(g_row[i][e], v[e], dot);
-          }
-          if (epd_dy) {
-            float o[NE];
-#pragma unroll
-            for (int e = 0; e < NE; ++e) o[e] = g * g_row[i][e];
-            R::store_round(epd_dy, (size_t)q, row_vecs, c, o);
-          }
+          for (int e = 0; e < NE; ++e) g_row[i][e] = 0.0f;
         }
       }
-      if (dw) {
-        dot = wave_sum_all(dot);
-        if (lane == s) my_dw = dot;
+      for (int s = 0; s < k; ++s) {
+        const int q = __builtin_amdgcn_readlane(my_q, s);
+        if (q < 0) continue;   // a plan that does not belong to these ids: nothing to address
+        const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_g), s));
+        float dot = 0.0f;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+          const int c = cbase + lane + 64 * i;
+          if (c < row_vecs) {
+            if (dw) {
+              float v[NE];
+              R::load(epd_y, (size_t)q, row_vecs, c, v);
+#pragma unroll
+              for (int e = 0; e < NE; ++e) dot = fmaf(g_row[i][e], v[e], dot);
+            }
+            if (epd_dy) {
+              float o[NE];
+#pragma unroll
+              for (int e = 0; e < NE; ++e) o[e] = g * g_row[i][e];
+              R::store_round(epd_dy, (size_t)q, row_vecs, c, o);
+            }
+          }
+        }
+        if (dw) {
+          dot = wave_sum_all(dot);
+          if (lane == s) my_dw += dot;
+        }
       }
     }
     if (dw && lane < k) dw[(size_t)t * k + lane] = my_dw;
@@ -202,8 +205,7 @@ extern "C" int occult_combine_backward(const occult_cfg_t* cfg, const occult_pla
   OCC_REQUIRE(row_bytes % 16 == 0, OCCULT_EALIGN, "row of %zu bytes is not a multiple of 16", row_bytes);
   OCC_REQUIRE(aligned16(dy) && aligned16(epd_y) && aligned16(epd_dy), OCCULT_EALIGN, "a buffer is not 16-byte aligned");
   const int row_vecs = (int)(row_bytes / 16);
-  const int vpl = (row_vecs + 63) / 64;
-  OCC_REQUIRE(vpl <= 8, OCCULT_EINVAL, "rows longer than 8 KiB are not supported (d=%d)", c.d);
+  const int vpl = (row_vecs + 63) / 64;   // beyond 8 the kernel walks the row in chunks of 8 KiB
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((c.T + kBwdWaves - 1) / kBwdWaves), block(kBwdWaves * 64);
 #define OCC_CBWD(B, N)                                                                                       \

@@ -32,12 +32,6 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
   const int wave = blockIdx.x * kCombWaves + (threadIdx.x >> 6);
   const int nwaves = gridDim.x * kCombWaves;
   for (int t = wave; t < T; t += nwaves) {
-    float acc[VPL][NE];
-#pragma unroll
-    for (int i = 0; i < VPL; ++i)
-#pragma unroll
-      for (int e = 0; e < NE; ++e) acc[i][e] = 0.0f;
-
     // The token's index lists in three wave-wide loads instead of one dependent load per entry
     // (D <= 64 and, when lists_fit, min(k, D) * M1 <= 64): lane j reads the SFD row on device j,
     // the rows are compacted in device order, lane (o, m) reads EPD row and gate m of the o-th one.
@@ -59,6 +53,13 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
       }
     }
 
+    // rows longer than 64 * VPL vectors are done in column chunks; the index lists stay in registers
+    for (int cbase = 0; cbase < row_vecs; cbase += 64 * VPL) {
+    float acc[VPL][NE];
+#pragma unroll
+    for (int i = 0; i < VPL; ++i)
+#pragma unroll
+      for (int e = 0; e < NE; ++e) acc[i][e] = 0.0f;
     for (int j = 0; j < n_dev; ++j) {
       int r;
       if (lists_fit) {
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
         }
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
-          const int c = lane + 64 * i;
+          const int c = cbase + lane + 64 * i;
           if (c < row_vecs) {
             float v[NE];
             R::load(epd_y, (size_t)q, row_vecs, c, v);
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
       // the return payload, then stage 2 on the rounded values
 #pragma unroll
       for (int i = 0; i < VPL; ++i) {
-        const int c = lane + 64 * i;
+        const int c = cbase + lane + 64 * i;
         if (c < row_vecs) {
           R::store_round(sfd_y, (size_t)r, row_vecs, c, part[i]);
 #pragma unroll
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
     }
 #pragma unroll
     for (int i = 0; i < VPL; ++i) {
-      const int c = lane + 64 * i;
+      const int c = cbase + lane + 64 * i;
       if (c < row_vecs) {
         if (y_shared) {
           float v[NE];
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
         R::store_round(y, (size_t)t, row_vecs, c, acc[i]);
       }
     }
+    }   // column chunks
   }
 }
 
@@ -131,8 +133,7 @@ static int launch_combine(const occult_cfg_t& c, const occult_plan_t* plan, cons
   OCC_REQUIRE(aligned16(epd) && aligned16(sfd) && aligned16(out) && aligned16(shared), OCCULT_EALIGN,
               "a buffer is not 16-byte aligned");
   const int row_vecs = (int)(row_bytes / 16);
-  const int vpl = (row_vecs + 63) / 64;
-  OCC_REQUIRE(vpl <= 8, OCCULT_EINVAL, "rows longer than 8 KiB are not supported by combine (d=%d)", c.d);
+  const int vpl = (row_vecs + 63) / 64;   // beyond 8 the kernel walks the row in chunks of 8 KiB
   hipStream_t s = static_cast<hipStream_t>(stream);
   const dim3 grid((c.T + kCombWaves - 1) / kCombWaves), block(kCombWaves * 64);
   const int M1 = merge_width(c);

@@ -25,6 +25,8 @@ CASES = [
     (8, 2, 2, 77, 8, "bf16", "contig"),          # 16-byte rows
     (8, 2, 2, 77, 4096, "bf16", "contig"),       # 8 KiB rows
     (8, 2, 2, 33, 1032, "f32", "random"),        # ragged vector count per lane
+    (8, 2, 2, 40, 8192, "bf16", "contig"),       # 16 KiB rows: two column chunks per row
+    (8, 4, 2, 21, 4104, "f32", "random"),        # 16.4 KiB rows: three chunks, the last ragged
     (8, 2, 2, 1, 64, "bf16", "contig"),          # one token
 ]
 
