@@ -41,6 +41,8 @@ SMALL = [
     ("bf16_few_rows_ragged", 80, 256, 192, 16, 2, 4, 4, "bf16"),
     # 256-row tiles with three K tiles, shared experts as uniform groups of the same kernel
     ("bf16_big_shared", 1100, 192, 128, 4, 3, 1, 4, "bf16"),
+    # hidden rows of 14 KiB (two column chunks in combine), long K in the first product
+    ("bf16_wide_rows", 200, 7168, 128, 32, 1, 4, 8, "bf16"),
 ]
 
 
