@@ -149,6 +149,23 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
       off_b[i] = (unsigned)(k * b_pitch + cb * 16);
       chunk_b[i] = (unsigned)(cb * 16);
     }
+    // the same for a step holding the group's last rows, or past them (issued to keep the load count constant)
+    auto issue_tail = [&](int s) {
+      const unsigned st = smem_base + (unsigned)(s % NST) * STAGE_BYTES;
+      const int row0 = r0 + s * BK;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int kb = wave * 8 + i * 2;               // tile rows kb, kb + 1
+        const long long ra = row0 + kb + rr;
+        // A: rows past the end read zeros
+        const char* src_a = (ra < r1) ? a_cols + ra * a_pitch + (off_a[i] - (unsigned)((kb + rr) * a_pitch)) : zeros;
+        load_to_lds_16(src_a, st + (unsigned)kb * 512u);
+        // B: rows past the end repeat the last row (the fetched indices are clamped the same way)
+        long long rb = min(row0 + kb + rr, r1 - 1);
+        if (GATHER) rb = s_idx[wave][s & 3][i * 2 + rr];
+        load_to_lds_16(b_cols + rb * b_pitch + chunk_b[i], st + (unsigned)OP_BYTES + (unsigned)kb * 512u);
+      }
+    };
     auto issue = [&](int s) {   // the 8 loads of this wave for step s into stage s % NST
       const unsigned st = smem_base + (unsigned)(s % NST) * STAGE_BYTES;
       const int row0 = r0 + s * BK;                    // first row of the step
@@ -166,19 +183,8 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
             load_to_lds_16(b_step, off_b[i], st + (unsigned)OP_BYTES + kb * 512u);
           }
         }
-      } else {                 // the group's last rows, and the steps past them that keep the load count constant
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int kb = wave * 8 + i * 2;               // tile rows kb, kb + 1
-          const long long ra = row0 + kb + rr;
-          // A: rows past the end read zeros
-          const char* src_a = (ra < r1) ? a_cols + ra * a_pitch + (off_a[i] - (unsigned)((kb + rr) * a_pitch)) : zeros;
-          load_to_lds_16(src_a, st + (unsigned)kb * 512u);
-          // B: rows past the end repeat the last row (the fetched indices are clamped the same way)
-          long long rb = min(row0 + kb + rr, r1 - 1);
-          if (GATHER) rb = s_idx[wave][s & 3][i * 2 + rr];
-          load_to_lds_16(b_cols + rb * b_pitch + chunk_b[i], st + (unsigned)OP_BYTES + (unsigned)kb * 512u);
-        }
+      } else {
+        issue_tail(s);
       }
     };
 
@@ -230,17 +236,59 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s);
     if (GATHER) issue_idx(NST);                          // into the slot step 0 has just been read from
-    for (int s = 0; s < nk; ++s) {
-      // Loads complete in order.  Per step a wave issues [indices of step s + NST + 1,] 8 tile loads of step
-      // s + NST - 1.  The tiles of step s are older than the (NST - 2) * OPS loads of the last NST - 2 steps;
-      // the indices used below (step s + NST - 1, issued first two steps ago) are older than all but one of them.
+    // Loads complete in order.  Per step a wave issues [indices of step s + NST + 1,] 8 tile loads of step
+    // s + NST - 1.  The tiles of step s are older than the (NST - 2) * OPS loads of the last NST - 2 steps;
+    // the indices used (step s + NST - 1, issued first two steps ago) are older than all but one of them.
+    // After the barrier every wave's tiles of step s are in LDS, and every wave is done with the stage that
+    // step s + NST - 1 overwrites.
+    // Two loops, so that neither has a branch inside (one would make the register allocator move the 256
+    // accumulators around): first the steps whose prefetched step lies wholly inside the group.
+    const int n_main = max(0, (r1 - r0) / BK - (NST - 1));
+    int s = 0;
+    for (; s < n_main; ++s) {
       wait_loads_and_barrier<(NST - 2) * OPS - (GATHER ? 1 : 0)>();
-      // after the barrier every wave's tiles of step s are in LDS, and every wave is done with the stage that
-      // step s + NST - 1 overwrites
+      bf16x8 fa[2][4], fbv[2][4];
+      read_frags(s, 0, fa[0], fbv[0]);
+      __builtin_amdgcn_sched_barrier(0);
+      const int sn = s + NST - 1;
+      if (GATHER) issue_idx(s + NST + 1);
+      // With one wave per SIMD nothing hides an instruction clump: the first half's 16 products are issued as
+      // 8 groups of {2 MFMAs, 1 tile load, 1 fragment read for the second half}, pinned in source order.
+      const unsigned st = smem_base + (unsigned)(sn % NST) * STAGE_BYTES;
+      const char* a_step = a_cols + (long long)(r0 + sn * BK) * a_pitch;
+      const char* b_step = b_cols + (long long)(r0 + sn * BK) * b_pitch;
+      const lds_char* As = (const lds_char*)smem + (s % NST) * STAGE_BYTES;
+      const lds_char* Bs = As + OP_BYTES;
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        const int mi = g >> 1, nj = (g & 1) * 2;
+        acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][mi], fbv[0][nj], acc[mi][nj], 0, 0, 0);
+        acc[mi][nj + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[0][mi], fbv[0][nj + 1], acc[mi][nj + 1], 0, 0, 0);
+        const int i = g & 3;
+        const unsigned kb = (unsigned)(wave * 8 + i * 2);
+        if (g < 4) {
+          load_to_lds_16(a_step, off_a[i], st + kb * 512u);
+          fa[1][g] = frag(As, wm * 128 + g * 32, 1);
+        } else {
+          if (GATHER) {
+            const long long rb = s_idx[wave][sn & 3][i * 2 + rr];   // fetched two steps ago
+            load_to_lds_16(b_cols + rb * b_pitch + chunk_b[i], st + (unsigned)OP_BYTES + kb * 512u);
+          } else {
+            load_to_lds_16(b_step, off_b[i], st + (unsigned)OP_BYTES + kb * 512u);
+          }
+          fbv[1][g - 4] = frag(Bs, wn * 128 + (g - 4) * 32, 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      mma(fa[1], fbv[1]);
+    }
+    // then the steps that prefetch the group's last rows or past them
+    for (; s < nk; ++s) {
+      wait_loads_and_barrier<(NST - 2) * OPS - (GATHER ? 1 : 0)>();
       bf16x8 fa[2][4], fbv[2][4];
       read_frags(s, 0, fa[0], fbv[0]);
       if (GATHER) issue_idx(s + NST + 1);
-      issue(s + NST - 1);      // address arithmetic and issue run while the first fragments arrive
+      issue_tail(s + NST - 1);
       read_frags(s, 1, fa[1], fbv[1]);
       mma(fa[0], fbv[0]);
       mma(fa[1], fbv[1]);
