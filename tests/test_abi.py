@@ -111,3 +111,33 @@ def test_host_placement_rejects_bad_shapes():
         B.occult_placement_greedy(np.zeros((8, 8), dtype=np.int32), 8)     # one expert per device
     with pytest.raises(B.OccultError):
         B.occult_placement_greedy(np.zeros((8, 8), dtype=np.int32), 3)
+
+
+def test_backward_and_packing_entry_points_validate_on_the_host(lib):
+    """Argument errors of the newer entry points are reported before any HIP call."""
+    good = dict(T=64, d=128, f=256, E=16, S=0, k=4, D=4, dtype="bf16")
+    cfg = B.make_cfg(**good)
+    # sizes: host, pure
+    assert B.occult_pack_weights_bytes(cfg) == 16 * 3 * 128 * 256 * 2
+    assert B.occult_pack_weights_bytes(B.make_cfg(**dict(good, dtype="f32"))) == 0
+    assert B.occult_expert_ffn_ws_bytes(cfg) == 0            # no shared experts: no scratch
+    # NULL arguments
+    assert lib.occult_combine_backward(ctypes.byref(cfg), None, None, None, None, None, None, None, None) == -4
+    assert lib.occult_dispatch_backward(ctypes.byref(cfg), None, None, None, None, None, None) == -4
+    assert lib.occult_route_backward(ctypes.byref(cfg), None, None, None, None, None) == -4
+    assert lib.occult_transpose_weights(ctypes.byref(cfg), None, None, None, None) == -4
+    assert lib.occult_pack_weights(ctypes.byref(cfg), None, None, 0, None) == -4
+    args11 = [None] * 11
+    assert lib.occult_expert_ffn_backward(ctypes.byref(cfg), None, None, None, None, *args11) == -4
+    assert lib.occult_expert_ffn_backward_weights(ctypes.byref(cfg), None, *args11, 0, None) == -4
+    assert lib.occult_expert_ffn_backward_weights(ctypes.byref(cfg), None, *args11, 2, None) in (-1, -4)
+    # a bad configuration is refused by every one of them
+    bad = B.make_cfg(**dict(good, D=5))
+    for call in (lambda: lib.occult_combine_backward(ctypes.byref(bad), None, None, None, None, None, None, None, None),
+                 lambda: lib.occult_transpose_weights(ctypes.byref(bad), None, None, None, None),
+                 lambda: lib.occult_pack_weights(ctypes.byref(bad), None, None, 0, None)):
+        assert call() == -2
+    # the bf16 expert kernels need d and f in multiples of 64
+    odd = B.make_cfg(**dict(good, d=72))
+    w = B.occult_weights_t(1 << 20, 1 << 20, 1 << 20)     # never dereferenced: the shape check comes first
+    assert lib.occult_pack_weights(ctypes.byref(odd), ctypes.byref(w), 1 << 20, 1 << 30, None) == -2
