@@ -93,6 +93,9 @@ def main():
                          "(measured: no faster on this runtime, 0.376 vs 0.363 ms on the decode workload)")
     ap.add_argument("--no-standard", action="store_true",
                     help="skip the comparison run with one simulated device per expert (standard dispatch)")
+    ap.add_argument("--placement", action="store_true",
+                    help="also run the layer with the greedy collaboration-aware placement of this batch's co-activation "
+                         "counts (always done for the large workload)")
     ap.add_argument("--no-pack", action="store_true",
                     help="decode-shaped workloads: read the weights in the caller's layout instead of the repacked copy")
     ap.add_argument("--no-backward", action="store_true",
@@ -345,6 +348,60 @@ def main():
             "occult_speedup_dispatch_plus_combine": (sc["dispatch"] + sc["combine"]) / (calls["dispatch"] + calls["combine"]),
         }
         layer = std
+    # Collaboration-aware placement (paper Sec. 3.2): the co-activation counts of this batch -> greedy placement on
+    # the host -> the same layer with that placement, against the contiguous one above.
+    if (args.workload == "large_bf16" or args.placement) and shape.E // shape.D >= 2 and shape.n_d == 0:
+        C.zero_()
+        ids_prof = torch.empty((T, k), dtype=torch.int32, device=dev)
+        w_prof = torch.empty((T, k), dtype=torch.float32, device=dev)
+        cfg0 = B.make_cfg(T, d, f, shape.E, S, k, shape.D, shape.dtype, 0, 1, shape.renorm, None)
+        B.occult_route(cfg0, logits, ids_prof, w_prof)
+        B.occult_coactivation(cfg0, ids_prof, C, False)
+        torch.cuda.synchronize()
+        _, pos = B.occult_placement_greedy(C.cpu().numpy(), shape.D)
+        del layer
+        torch.cuda.empty_cache()
+        gr = OccultLayer(T, d, f, shape.E, S, k, shape.D, shape.dtype, 0, 1, shape.renorm, pos)
+        if packed_weights:
+            gr.pack_weights(wg, wu, wd)
+        gr.route(logits)
+        gr.make_plan()
+        gr.dispatch(x)
+        gr.expert_ffn(x, wg, wu, wd)
+        gc = {
+            "plan": _event_time_ms(lambda: gr.make_plan(), r),
+            "dispatch": _event_time_ms(lambda: gr.dispatch(x), r),
+            "expert_ffn": _event_time_ms(lambda: gr.expert_ffn(x, wg, wu, wd), r),
+            "combine": _event_time_ms(lambda: gr.combine(), r),
+        }
+        gst = gr.stats()
+        g3 = gc["dispatch"] + gc["expert_ffn"] + gc["combine"]
+        out["greedy_placement"] = {
+            "c_t": gst.c_t, "c_t_contiguous": st.c_t, "bytes_per_token": gst.bytes_occ / T,
+            "bytes_per_token_contiguous": st.bytes_occ / T, "saved_fraction_vs_contiguous": 1.0 - gst.bytes_occ / st.bytes_occ,
+            "calls_ms": gc, "tokens_per_s_dispatch_ffn_combine": T / (g3 * 1e-3),
+            "speedup_dispatch_plus_combine": (calls["dispatch"] + calls["combine"]) / (gc["dispatch"] + gc["combine"]),
+        }
+        layer = gr
+    # Collaboration pruning (paper Sec. 3.3): the same layer without pruning, for the routing change, the bytes
+    # and the difference of the outputs.
+    if shape.n_d > 0:
+        y_pruned = layer.y.float().clone() if getattr(layer, "y", None) is not None else None
+        ids_pruned = layer.ids.clone()
+        del layer
+        torch.cuda.empty_cache()
+        un = OccultLayer(T, d, f, shape.E, S, k, shape.D, shape.dtype, 0, 1, shape.renorm, None)
+        y_un = un.forward(logits, x, wg, wu, wd).float()
+        torch.cuda.synchronize()
+        ust = un.stats()
+        same = (ids_pruned.sort(dim=1).values == un.ids.sort(dim=1).values).all(dim=1).float().mean().item()
+        out["pruning"] = {
+            "n_d": shape.n_d, "prune_mode": shape.prune_mode, "c_t": st.c_t, "c_t_unpruned": ust.c_t,
+            "bytes_per_token": st.bytes_occ / T, "bytes_per_token_unpruned": ust.bytes_occ / T,
+            "tokens_with_unchanged_experts": same,
+            "output_rel_l2_diff_vs_unpruned": ((y_pruned - y_un).norm() / y_un.norm()).item(),
+        }
+        layer = un
     if not args.no_cpu_baseline:
         del layer
         out["cpu_baseline"] = cpu_baseline(wk, shape, args.cpu_sample)
