@@ -279,11 +279,21 @@ def main():
         bc["transpose_weights"] = _event_time_ms(lambda: layer.transpose_weights(wg, wu, wd), r)
         bc["expert_ffn_backward"] = _event_time_ms(lambda: layer.expert_ffn_backward(x, wg, wu, layer.epd_dy, dy), r)
         bc["expert_ffn_backward_weights"] = _event_time_ms(lambda: layer.expert_ffn_backward_weights(x, dy), r)
+        # the alternative for a training step: the forward call keeps the pre-activations, the backward does not recompute
+        bc["expert_ffn_train"] = _event_time_ms(lambda: layer.expert_ffn_train(x, wg, wu, wd), r)
+        bc["expert_ffn_backward_kept"] = _event_time_ms(
+            lambda: layer.expert_ffn_backward(x, wg, wu, layer.epd_dy, dy, gu_saved=True), r)
         rows_ffn = n_epd + S * T
-        fb = {"expert_ffn_backward": 10.0 * d * f * rows_ffn, "expert_ffn_backward_weights": 6.0 * d * f * rows_ffn}
+        fb = {"expert_ffn_backward": 10.0 * d * f * rows_ffn, "expert_ffn_backward_weights": 6.0 * d * f * rows_ffn,
+              "expert_ffn_train": 6.0 * d * f * rows_ffn, "expert_ffn_backward_kept": 6.0 * d * f * rows_ffn}
         bb["transpose_weights"] = 2.0 * 3 * (shape.E + S) * d * f * es
         bc["backward_total"] = (bc["combine_backward"] + bc["expert_ffn_backward"] + bc["expert_ffn_backward_weights"]
                                 + bc["dispatch_backward"] + bc["route_backward"])
+        # forward + backward of one training step with kept pre-activations, against recomputing them
+        fwd_rest = calls["route"] + calls["plan"] + calls["dispatch"] + calls["combine"]
+        bc["train_step_kept"] = (fwd_rest + bc["expert_ffn_train"] + bc["backward_total"] - bc["expert_ffn_backward"]
+                                 + bc["expert_ffn_backward_kept"])
+        bc["train_step_recompute"] = fwd_rest + calls["expert_ffn"] + bc["backward_total"]
         backward = {"calls_ms": bc,
                     "rooflines": {n: {"bound": "hbm", "achieved": gbs(bb[n], bc[n]), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                       "frac": gbs(bb[n], bc[n]) / PEAK_HBM_GBS} for n in bb}}

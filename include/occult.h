@@ -282,7 +282,8 @@ int occult_dispatch_backward(const occult_cfg_t* cfg, const occult_plan_t* plan,
  * side by side.  Call it again whenever the weights change.
  *
  * occult_expert_ffn_backward: for EPD row q of the expert at position P, x_q = sfd_x[epd_sfd_row[q]]:
- *   g = W_gate x_q, u = W_up x_q (recomputed, rounded to cfg.dtype), dh = W_down^T epd_dy[q],
+ *   g = W_gate x_q, u = W_up x_q (recomputed, or as kept by occult_expert_ffn_train when gu_saved = 1;
+ *   rounded to cfg.dtype), dh = W_down^T epd_dy[q],
  *   dg = dh * u * silu'(g), du = dh * silu(g), epd_dx[q] = W_gate^T dg + W_up^T du.
  * epd_dy [N_epd][d] is occult_combine_backward's (gate-scaled) output.  Outputs: epd_dx [N_epd][d], and
  * epd_gu [N_epd][2f] = [dg | du] (the operand a weight-gradient product needs); epd_dh [N_epd][f] is
@@ -297,7 +298,19 @@ int occult_expert_ffn_backward(const occult_cfg_t* cfg, const occult_plan_t* pla
                                const void* x, const occult_weights_t* weights, const void* w_down_t,
                                const void* w_gu_t, const void* epd_dy, const void* dy, void* epd_gu,
                                void* epd_dh, void* epd_dx, void* gu_shared, void* dh_shared,
-                               void* dx_shared, occult_stream_t stream);
+                               void* dx_shared, int gu_saved, occult_stream_t stream);
+
+/* Forward pass of a training step: occult_expert_ffn_ws that also keeps the pre-activations, so that
+ * the backward pass need not recompute them: epd_gu [N_epd][2f] = [g | u] per EPD row and, with shared
+ * experts, gu_shared [T][S*2f] = per shared expert [g | u] (rounded to cfg.dtype).  On 256-row tiles
+ * the first product stores them from the same accumulators; the other kernels add two products.
+ * Pass gu_saved = 1 to occult_expert_ffn_backward afterwards (it overwrites both with [dg | du]);
+ * gu_saved = 0 recomputes g and u there (0.5 GB less memory held between the passes at the prefill
+ * size, for about a fifth more backward time). */
+int occult_expert_ffn_train(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                            const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
+                            void* h_shared, void* y_shared, void* epd_gu, void* gu_shared, void* ws,
+                            size_t ws_bytes, occult_stream_t stream);
 
 /* Weight gradients of occult_expert_ffn (same sources; f32 outputs in the layout of the weights:
  * dw_gate, dw_up [E+S][f][d], dw_down [E+S][d][f], device ptrs).  For the expert at position P with

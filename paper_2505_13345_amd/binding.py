@@ -25,7 +25,7 @@ EXPORTS = [
     "occult_similarity_gram", "occult_similarity_table", "occult_expert_ffn_ws_bytes", "occult_expert_ffn_ws",
     "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
     "occult_transpose_weights", "occult_expert_ffn_backward", "occult_expert_ffn_backward_weights",
-    "occult_pack_weights_bytes", "occult_pack_weights", "occult_expert_ffn_packed",
+    "occult_pack_weights_bytes", "occult_pack_weights", "occult_expert_ffn_packed", "occult_expert_ffn_train",
 ]
 
 
@@ -101,7 +101,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_dispatch_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_route_backward.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_transpose_weights.argtypes = [cfgp, POINTER(occult_weights_t), c_void_p, c_void_p, c_void_p]
-    lib.occult_expert_ffn_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t)] + [c_void_p] * 11
+    lib.occult_expert_ffn_backward.argtypes = ([cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t)] + [c_void_p] * 10
+                                              + [c_int, c_void_p])
+    lib.occult_expert_ffn_train.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t)] + [c_void_p] * 7 + [
+        c_size_t, c_void_p]
     lib.occult_expert_ffn_backward_weights.argtypes = [cfgp, planp] + [c_void_p] * 11 + [c_int, c_void_p]
     lib.occult_coactivation.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_placement_greedy.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
@@ -270,13 +273,24 @@ def occult_transpose_weights(cfg, w_gate, w_up, w_down, w_down_t, w_gu_t, stream
                                                    _stream(stream)))
 
 
+def occult_expert_ffn_train(cfg, plan, sfd_x, x, w_gate, w_up, w_down, epd_h, epd_y, h_shared, y_shared, epd_gu, gu_shared,
+                            ws=None, stream=None) -> None:
+    wts = occult_weights_t(_ptr(w_gate), _ptr(w_up), _ptr(w_down))
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().occult_expert_ffn_train(ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x),
+                                                  ctypes.byref(wts), _ptr(epd_h), _ptr(epd_y), _ptr(h_shared),
+                                                  _ptr(y_shared), _ptr(epd_gu), _ptr(gu_shared), _ptr(ws), nbytes,
+                                                  _stream(stream)))
+
+
 def occult_expert_ffn_backward(cfg, plan, sfd_x, x, w_gate, w_up, w_down_t, w_gu_t, epd_dy, dy, epd_gu, epd_dh, epd_dx,
-                               gu_shared=None, dh_shared=None, dx_shared=None, stream=None) -> None:
+                               gu_shared=None, dh_shared=None, dx_shared=None, gu_saved=False, stream=None) -> None:
     wts = occult_weights_t(_ptr(w_gate), _ptr(w_up), None)
     _check(load_library().occult_expert_ffn_backward(ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x),
                                                      ctypes.byref(wts), _ptr(w_down_t), _ptr(w_gu_t), _ptr(epd_dy),
                                                      _ptr(dy), _ptr(epd_gu), _ptr(epd_dh), _ptr(epd_dx), _ptr(gu_shared),
-                                                     _ptr(dh_shared), _ptr(dx_shared), _stream(stream)))
+                                                     _ptr(dh_shared), _ptr(dx_shared), int(bool(gu_saved)),
+                                                     _stream(stream)))
 
 
 def occult_expert_ffn_backward_weights(cfg, plan, sfd_x, x, epd_h, h_shared, epd_dy, dy, epd_gu, gu_shared, dw_gate,

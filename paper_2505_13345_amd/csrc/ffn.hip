@@ -474,6 +474,7 @@ __device__ __forceinline__ float swiglu_fast(float g, float u) {
 // One output tile before its row gather has come back.  All fields but raw are wave-uniform.
 struct Head {
   int valid, m0, rows, row_base, n0, widx, ccol;   // ccol: first output column of the tile's group
+  int ccol2;                                        // the same in the pre-activation output (SAVE)
   int raw[8];   // source rows of this lane's 8 A-tile rows
 };
 
@@ -508,8 +509,9 @@ __device__ __forceinline__ void locate(const GemmArgs& a, const int* s_goff, con
 }
 
 
-template <bool SWIGLU>
+template <bool SWIGLU, bool SAVE>   // SAVE (with SWIGLU): the gate and up pre-activations are stored too (a.C2)
 __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
+  static_assert(SWIGLU || !SAVE, "pre-activations exist only with the fused activation");
   __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
   __shared__ int s_goff[OCCULT_MAX_E + 1];   // group row offsets
   __shared__ int s_widx[OCCULT_MAX_E];       // weight matrix of each group
@@ -552,14 +554,17 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     h.n0 = tm.nt * BN_OUT;
     h.widx = a.w_base;
     h.ccol = a.c_col0;
+    h.ccol2 = a.c2_col0;
     if (h.valid) {
       h.widx = a.grp_offset ? s_widx[group] : a.w_base + group;
       h.ccol = group_col0(a, group);
+      h.ccol2 = a.c2_col0 + group * a.c2_group_cols;
     } else if (fallback) {
       h.m0 = fallback->m0; h.rows = fallback->rows; h.row_base = fallback->row_base;
-      h.n0 = fallback->n0; h.widx = fallback->widx; h.ccol = fallback->ccol;
+      h.n0 = fallback->n0; h.widx = fallback->widx; h.ccol = fallback->ccol; h.ccol2 = fallback->ccol2;
     }
     h.ccol = __builtin_amdgcn_readfirstlane(h.ccol);
+    h.ccol2 = __builtin_amdgcn_readfirstlane(h.ccol2);
     h.widx = __builtin_amdgcn_readfirstlane(h.widx);
     h.m0 = __builtin_amdgcn_readfirstlane(h.m0);
     h.rows = __builtin_amdgcn_readfirstlane(h.rows);
@@ -849,6 +854,57 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       read_chunk(NCH - 1);
       store_chunk(NCH - 1);
       __builtin_amdgcn_sched_barrier(0);
+      if (SAVE) {
+        // The pre-activations for a training step's backward pass: 8 more chunks (row block, gate or up) of
+        // 32 rows x 64 columns through the same two buffers, to rows of [gate | up] (the up half c2_up
+        // columns further).  One descriptor spans both halves of the wave tile's valid rows; an invalid row
+        // lies past it because a row of the output is longer than c2_up + 64 columns (f >= 64).
+        const unsigned n_rec2 = rows_left > 0 ? (unsigned)((rows_left - 1) * a.ldc2 + a.c2_up + W_COLS) * 2u : 0u;
+        const unsigned long long c2_tile = reinterpret_cast<unsigned long long>(
+            static_cast<__bf16*>(a.C2) + (long long)(hd.row_base + hd.m0 + wm * 128) * a.ldc2 + hd.ccol2 + col_w);
+        const unsigned long long c2_tile_u =
+            ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c2_tile >> 32)) << 32) |
+            (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c2_tile);
+        const __amdgpu_buffer_rsrc_t c2_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            reinterpret_cast<void*>(c2_tile_u), 0, __builtin_amdgcn_readfirstlane((int)n_rec2), 0x00020000);
+        auto stage_pre = [&](int c) {
+          char* buf = wr + (c & 1) * 4096;
+          const int mi = c >> 1, hh = c & 1;   // hh: 0 gate, 1 up
+#pragma unroll
+          for (int nn = 0; nn < 2; ++nn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              uint2 pk;
+              pk.x = pack_bf16(acc[2 * nn + hh][mi][q * 4 + 0], acc[2 * nn + hh][mi][q * 4 + 1]);
+              pk.y = pack_bf16(acc[2 * nn + hh][mi][q * 4 + 2], acc[2 * nn + hh][mi][q * 4 + 3]);
+              *reinterpret_cast<uint2*>(buf + (((nn * 4 + q) ^ wsw) * 16)) = pk;
+            }
+        };
+        auto store_pre = [&](int c) {
+          const int mi = c >> 1, hh = c & 1;
+          const int col = rch * 8;   // inside the wave tile's 64 output columns
+#pragma unroll
+          for (int it = 0; it < 4; ++it) {
+            const int row = mi * 32 + it * 8 + rrow;
+            const unsigned off = col_w + col < a.N ? (unsigned)(row * a.ldc2 + col + hh * a.c2_up) * 2u : n_rec2;
+            __builtin_amdgcn_raw_buffer_store_b128(sv[it], c2_rsrc, (int)off, 0, 0);
+          }
+        };
+        stage_pre(0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 1; c < 8; ++c) {
+          read_chunk(c - 1);
+          __builtin_amdgcn_sched_barrier(0);
+          stage_pre(c);
+          __builtin_amdgcn_sched_barrier(0);
+          store_pre(c - 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        read_chunk(7);
+        store_pre(7);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     if (!hn.valid) break;   // uniform over the block
     hd = hn;
@@ -997,8 +1053,10 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const u32x4* __restri
   }
 }
 
-int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
-  if (total_rows == 0) return OCCULT_OK;
+// *fused_save: the pre-activations asked for through a.C2 were written by the launch itself
+static int launch_gemm_main(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s,
+                            bool* fused_save_out) {
+  *fused_save_out = false;
   if (c.dtype == OCCULT_BF16) {
     const int groups = a.ngroups;
     // 256-row tiles once groups average enough rows, every A byte offset fits 32 bits and there
@@ -1009,6 +1067,8 @@ int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total
     const long long big_rows = a.grp_offset == nullptr ? 192 : (swiglu ? 129 : 64);
     const bool use_big = (long long)total_rows >= big_rows * groups && a.ksplit <= 1 &&
                          (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK;
+    const bool fused_save = swiglu && a.C2 != nullptr && use_big;   // only the 256-row tiles store them themselves
+    *fused_save_out = fused_save;
     // groups averaging under 24 rows: weight streaming, one wave per 32 columns x 32 tokens
     const bool use_skinny = !use_big && (long long)total_rows < 24ll * groups && a.N % skinny::BN_OUT == 0;
     if (use_skinny) {
@@ -1048,8 +1108,9 @@ int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total
     }
     const dim3 grid((unsigned)blocks, split ? (unsigned)b.ksplit : 1u), block(256);
     if (use_big) {
-      if (swiglu) hipLaunchKernelGGL(t256::grouped_gemm_bf16<true>, grid, block, 0, s, b);
-      else hipLaunchKernelGGL(t256::grouped_gemm_bf16<false>, grid, block, 0, s, b);
+      if (swiglu && fused_save) hipLaunchKernelGGL((t256::grouped_gemm_bf16<true, true>), grid, block, 0, s, b);
+      else if (swiglu) hipLaunchKernelGGL((t256::grouped_gemm_bf16<true, false>), grid, block, 0, s, b);
+      else hipLaunchKernelGGL((t256::grouped_gemm_bf16<false, false>), grid, block, 0, s, b);
     } else {
       if (swiglu) hipLaunchKernelGGL(small::grouped_gemm_bf16<true>, grid, block, 0, s, b);
       else hipLaunchKernelGGL(small::grouped_gemm_bf16<false>, grid, block, 0, s, b);
@@ -1071,6 +1132,24 @@ int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total
   }
   OCC_LAUNCH_CHECK("grouped_gemm");
   return OCCULT_OK;
+}
+
+int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
+  if (total_rows == 0) return OCCULT_OK;
+  bool fused_save = false;
+  int rc = launch_gemm_main(c, a, swiglu, total_rows, s, &fused_save);
+  if (rc) return rc;
+  if (swiglu && a.C2 != nullptr && !fused_save) {
+    // the other kernels do not store pre-activations: two more products without the activation
+    GemmArgs p = a;
+    p.C = a.C2; p.ldc = a.ldc2; p.c_group_cols = a.c2_group_cols; p.C2 = nullptr; p.B2 = nullptr; p.Bp = nullptr;
+    p.c_col0 = a.c2_col0;
+    rc = launch_gemm_main(c, p, false, total_rows, s, &fused_save);
+    if (rc) return rc;
+    p.B = a.B2; p.c_col0 = a.c2_col0 + a.c2_up;
+    rc = launch_gemm_main(c, p, false, total_rows, s, &fused_save);
+  }
+  return rc;
 }
 
 }  // namespace occult
@@ -1103,7 +1182,7 @@ extern "C" int occult_expert_ffn_ws_bytes(const occult_cfg_t* cfg, size_t* ws_by
 static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
                            const void* x, const occult_weights_t* weights, const void* packed, void* epd_h,
                            void* epd_y, void* h_shared, void* y_shared, void* ws, size_t ws_bytes,
-                           occult_stream_t stream) {
+                           occult_stream_t stream, void* epd_gu = nullptr, void* gu_shared = nullptr) {
   int rc = check_cfg(cfg);
   if (rc) return rc;
   const occult_cfg_t c = *cfg;
@@ -1140,6 +1219,7 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
       a1.B = weights->w_gate; a1.B2 = weights->w_up;
       a1.b_group_stride = (long long)c.f * c.d; a1.ldb = c.d; a1.kseg = c.d;
       a1.C = h_shared; a1.ldc = c.S * c.f; a1.c_col0 = 0; a1.c_group_cols = c.f;
+      a1.C2 = gu_shared; a1.ldc2 = c.S * 2 * c.f; a1.c2_col0 = 0; a1.c2_group_cols = 2 * c.f; a1.c2_up = c.f;
       a1.grp_offset = nullptr; a1.grp_widx = nullptr; a1.w_base = c.E;
       a1.ngroups = c.S; a1.M = c.T; a1.N = c.f; a1.K = c.d; a1.a_rows_total = c.T;
       const int r1 = launch_gemm(c, a1, true, c.T * c.S, s_shared);
@@ -1171,6 +1251,7 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
       g1.b_group_stride = (long long)c.f * c.d; g1.ldb = c.d; g1.kseg = c.d;
       g1.Bp = packed; g1.bp_group_stride = 4ll * c.f * c.d;
       g1.C = epd_h; g1.ldc = c.f; g1.c_col0 = 0;
+      g1.C2 = epd_gu; g1.ldc2 = 2 * c.f; g1.c2_col0 = 0; g1.c2_group_cols = 0; g1.c2_up = c.f;
       g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.w_base = 0;
       g1.ngroups = c.E; g1.M = 0; g1.N = c.f; g1.K = c.d;
       g1.a_rows_total = sfd_rows_max(c);
@@ -1214,6 +1295,17 @@ extern "C" int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t
                                     occult_stream_t stream) {
   if (ws != nullptr) OCC_REQUIRE(aligned16(ws), OCCULT_EALIGN, "ws is not 16-byte aligned");
   return expert_ffn_impl(cfg, plan, sfd_x, x, weights, nullptr, epd_h, epd_y, h_shared, y_shared, ws, ws_bytes, stream);
+}
+
+extern "C" int occult_expert_ffn_train(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                       const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
+                                       void* h_shared, void* y_shared, void* epd_gu, void* gu_shared, void* ws,
+                                       size_t ws_bytes, occult_stream_t stream) {
+  OCC_REQUIRE(epd_gu != nullptr, OCCULT_ENULLPTR, "epd_gu is NULL");
+  OCC_REQUIRE(cfg == nullptr || cfg->S == 0 || gu_shared != nullptr, OCCULT_ENULLPTR, "gu_shared is NULL with shared experts");
+  OCC_REQUIRE(aligned16(epd_gu) && aligned16(gu_shared) && aligned16(ws), OCCULT_EALIGN, "a buffer is not 16-byte aligned");
+  return expert_ffn_impl(cfg, plan, sfd_x, x, weights, nullptr, epd_h, epd_y, h_shared, y_shared, ws, ws_bytes, stream,
+                         epd_gu, gu_shared);
 }
 
 static size_t packed_bytes(const occult_cfg_t& c) {

@@ -176,7 +176,7 @@ extern "C" int occult_expert_ffn_backward(const occult_cfg_t* cfg, const occult_
                                           const void* x, const occult_weights_t* weights, const void* w_down_t,
                                           const void* w_gu_t, const void* epd_dy, const void* dy, void* epd_gu,
                                           void* epd_dh, void* epd_dx, void* gu_shared, void* dh_shared,
-                                          void* dx_shared, occult_stream_t stream) {
+                                          void* dx_shared, int gu_saved, occult_stream_t stream) {
   int rc = check_cfg(cfg);
   if (rc) return rc;
   const occult_cfg_t c = *cfg;
@@ -205,7 +205,8 @@ extern "C" int occult_expert_ffn_backward(const occult_cfg_t* cfg, const occult_
   GemmArgs base{};
   base.grp_offset = plan->exp_offset; base.grp_widx = plan->pos_expert; base.w_base = 0;
   base.ngroups = c.E; base.M = 0;
-  {   // g | u: the forward's first product without its SwiGLU epilogue, gate then up
+  OCC_REQUIRE(gu_saved == 0 || gu_saved == 1, OCCULT_EINVAL, "gu_saved=%d must be 0 or 1", gu_saved);
+  if (!gu_saved) {   // g | u: the forward's first product without its SwiGLU epilogue, gate then up
     GemmArgs a = base;
     a.A = sfd_x; a.lda = c.d; a.a_rows = plan->epd_sfd_row; a.a_rows_total = sfd_rows_max(c);
     a.b_group_stride = mat; a.ldb = c.d; a.kseg = c.d;
@@ -241,7 +242,7 @@ extern "C" int occult_expert_ffn_backward(const occult_cfg_t* cfg, const occult_
   GemmArgs sh{};
   sh.grp_offset = nullptr; sh.grp_widx = nullptr; sh.w_base = c.E; sh.ngroups = c.S; sh.M = c.T;
   sh.a_rows = nullptr; sh.a_rows_total = c.T;
-  {
+  if (!gu_saved) {
     GemmArgs a = sh;
     a.A = x; a.lda = c.d;
     a.b_group_stride = mat; a.ldb = c.d; a.kseg = c.d;

@@ -88,15 +88,28 @@ class OccultLayer:
             B.occult_expert_ffn(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h,
                                 self.epd_y, self.h_shared, self.y_shared)
 
+    def expert_ffn_train(self, x, w_gate, w_up, w_down):
+        """expert_ffn() that also keeps the pre-activations [g | u] for expert_ffn_backward(gu_saved=True)."""
+        s = self.shape
+        T, k, f, S = s["T"], s["k"], s["f"], s["S"]
+        epd_gu = self._buf("epd_gu", (T * k, 2 * f), self.tdtype)
+        gu_sh = self._buf("gu_shared", (T, S * 2 * f), self.tdtype) if S > 0 else None
+        B.occult_expert_ffn_train(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h, self.epd_y,
+                                  self.h_shared, self.y_shared, epd_gu, gu_sh, self.ffn_ws)
+        self.gu_saved = True
+
     def combine(self, epd_y=None):
         B.occult_combine(self.cfg, self.plan, self.epd_y if epd_y is None else epd_y, self.sfd_y,
                          self.y_shared, self.y)
 
-    def forward(self, logits, x, w_gate, w_up, w_down):
+    def forward(self, logits, x, w_gate, w_up, w_down, train=False):
         self.route(logits)
         self.make_plan()
         self.dispatch(x)
-        self.expert_ffn(x, w_gate, w_up, w_down)
+        if train:
+            self.expert_ffn_train(x, w_gate, w_up, w_down)
+        else:
+            self.expert_ffn(x, w_gate, w_up, w_down)
         self.combine()
         return self.y
 
@@ -133,7 +146,7 @@ class OccultLayer:
         B.occult_transpose_weights(self.cfg, w_gate, w_up, w_down, w_down_t, w_gu_t)
         return w_down_t, w_gu_t
 
-    def expert_ffn_backward(self, x, w_gate, w_up, epd_dy, dy):
+    def expert_ffn_backward(self, x, w_gate, w_up, epd_dy, dy, gu_saved=None):
         """epd_dy [T*k, d] (and dy [T, d] for shared experts) -> epd_dx, dx_shared (None if S == 0);
         needs transpose_weights() first and the forward's sfd_x."""
         s = self.shape
@@ -146,8 +159,11 @@ class OccultLayer:
             gu_sh = self._buf("gu_shared", (T, S * 2 * f), self.tdtype)
             dh_sh = self._buf("dh_shared", (T, S * f), self.tdtype)
             dx_sh = self._buf("dx_shared", (T, d), self.tdtype)
+        if gu_saved is None:   # pre-activations kept by expert_ffn_train() since the last backward
+            gu_saved = getattr(self, "gu_saved", False)
         B.occult_expert_ffn_backward(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, self.w_down_t, self.w_gu_t,
-                                     epd_dy, dy, epd_gu, epd_dh, epd_dx, gu_sh, dh_sh, dx_sh)
+                                     epd_dy, dy, epd_gu, epd_dh, epd_dx, gu_sh, dh_sh, dx_sh, gu_saved)
+        self.gu_saved = False      # overwritten with [dg | du]
         return epd_dx, dx_sh
 
     def expert_ffn_backward_weights(self, x, dy, accumulate=False):

@@ -128,7 +128,7 @@ def test_backward_and_packing_entry_points_validate_on_the_host(lib):
     assert lib.occult_transpose_weights(ctypes.byref(cfg), None, None, None, None) == -4
     assert lib.occult_pack_weights(ctypes.byref(cfg), None, None, 0, None) == -4
     args11 = [None] * 11
-    assert lib.occult_expert_ffn_backward(ctypes.byref(cfg), None, None, None, None, *args11) == -4
+    assert lib.occult_expert_ffn_backward(ctypes.byref(cfg), None, None, None, None, *([None] * 10), 0, None) == -4
     assert lib.occult_expert_ffn_backward_weights(ctypes.byref(cfg), None, *args11, 0, None) == -4
     assert lib.occult_expert_ffn_backward_weights(ctypes.byref(cfg), None, *args11, 2, None) in (-1, -4)
     # a bad configuration is refused by every one of them

@@ -199,3 +199,51 @@ def test_ffn_backward_argument_checks():
     empty = OccultLayer(0, 64, 64, 4, 0, 2, 2, "bf16")
     B.occult_expert_ffn_backward(empty.cfg, empty.plan, None, None, None, None, None, None, None, None, None, None, None)
     torch.cuda.synchronize()
+
+
+KEEP_CASES = [
+    ("bf16_a", 700, 256, 192, 8, 0, 2, 4, "bf16"),                  # 256-row tiles: stored by the first product itself
+    ("bf16_big_shared", 1100, 192, 128, 4, 3, 1, 4, "bf16"),        # the same with shared experts as uniform groups
+    ("bf16_few_rows_ragged", 80, 256, 192, 16, 2, 4, 4, "bf16"),    # other kernels: two more products
+    ("f32_shared", 130, 128, 256, 16, 2, 4, 4, "f32"),
+]
+
+
+@pytest.mark.parametrize("name,T,d,f,E,S,k,D,dtype", KEEP_CASES)
+def test_kept_preactivations_give_the_recomputed_gradients(name, T, d, f, E, S, k, D, dtype):
+    """occult_expert_ffn_train + gu_saved = 1 against the recomputing backward (itself compared with the
+    oracle above): same forward outputs, same gradients, bit for bit (the kept values are rounded from
+    the same accumulators the recomputation produces)."""
+    say(f"kept pre-activations {name}")
+    dev = require_gpu()
+    shape = wl.LayerShape(name, T=T, d=d, f=f, E=E, S=S, k=k, D=D, dtype=dtype, components=4 if dtype == "bf16" else 0)
+    wk = wl.make_workload(shape, seed=17)
+    pos = wl.random_placement(E, D, seed=2)
+    dy = np.random.default_rng(T).standard_normal((T, d)).astype(np.float32)
+    if dtype == "bf16":
+        dy = wl.round_to_bf16(dy)
+    x = to_dev(wk.x, dtype, dev)
+    wg, wu, wd = (to_dev(a, dtype, dev) for a in (wk.w_gate, wk.w_up, wk.w_down))
+    dy_d = to_dev(dy, dtype, dev)
+    logits = torch.from_numpy(wk.logits).to(dev)
+    results = []
+    for train in (False, True):
+        layer = OccultLayer(T, d, f, E, S, k, D, dtype, expert_pos=pos)
+        y = layer.forward(logits, x, wg, wu, wd, train=train).clone()
+        gu_fwd = layer.epd_gu.clone() if train else None
+        layer.transpose_weights(wg, wu, wd)
+        dx, dw = layer.backward_input(x, wg, wu, dy_d)
+        grads = layer.expert_ffn_backward_weights(x, dy_d)
+        torch.cuda.synchronize()
+        assert getattr(layer, "gu_saved", False) is False
+        results.append(dict(y=y, h=layer.epd_h.clone(), dx=dx.clone(), dw=dw.clone(), gu=layer.epd_gu.clone(),
+                            epd_dx=layer.epd_dx.clone(), grads=[g.clone() for g in grads], gu_fwd=gu_fwd,
+                            dx_sh=layer.dx_shared.clone() if S else None))
+    a, b = results
+    for key in ("y", "h", "dx", "dw", "gu", "epd_dx"):
+        assert torch.equal(a[key], b[key]), key
+    for ga, gb in zip(a["grads"], b["grads"]):
+        assert torch.equal(ga, gb)
+    if S:
+        assert torch.equal(a["dx_sh"], b["dx_sh"])
+    assert b["gu_fwd"].float().abs().max() > 0          # the kept values were really written by the forward call
