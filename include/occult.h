@@ -57,7 +57,7 @@ typedef void* occult_stream_t; /* a hipStream_t */
 
 /* Layer description.  Plain data; copied by value inside each call. */
 typedef struct occult_cfg {
-  int32_t T;          /* tokens (ORI rows), >= 0; T * k < 2^31                              */
+  int32_t T;          /* tokens (ORI rows), >= 0; T * k < 2^31 and T * S < 2^31              */
   int32_t d;          /* hidden size                                                        */
   int32_t f;          /* expert intermediate size                                           */
   int32_t E;          /* routed experts, 1..OCCULT_MAX_E, E % D == 0                        */

@@ -26,6 +26,7 @@ int check_cfg(const occult_cfg_t* cfg) {
               "k=%d outside 1..min(E=%d, %d)", c.k, c.E, OCCULT_MAX_K);
   OCC_REQUIRE((int64_t)c.T * c.k < (int64_t)INT32_MAX, OCCULT_EINVAL, "T*k overflows int32");
   OCC_REQUIRE(c.S >= 0 && c.S <= 64, OCCULT_EINVAL, "S=%d outside 0..64", c.S);
+  OCC_REQUIRE((int64_t)c.T * c.S < (int64_t)INT32_MAX, OCCULT_EINVAL, "T*S overflows int32");
   OCC_REQUIRE(c.d >= 1 && c.f >= 1, OCCULT_EINVAL, "d=%d, f=%d must be positive", c.d, c.f);
   OCC_REQUIRE(c.dtype == OCCULT_F32 || c.dtype == OCCULT_BF16, OCCULT_EINVAL, "unknown dtype %d", c.dtype);
   OCC_REQUIRE(c.n_d >= 0 && c.n_d <= c.D, OCCULT_EINVAL, "n_d=%d outside 0..D=%d", c.n_d, c.D);
