@@ -474,7 +474,6 @@ __device__ __forceinline__ float swiglu_fast(float g, float u) {
 // One output tile before its row gather has come back.  All fields but raw are wave-uniform.
 struct Head {
   int valid, m0, rows, row_base, n0, widx, ccol;   // ccol: first output column of the tile's group
-  int ccol2;                                        // the same in the pre-activation output (SAVE)
   int raw[8];   // source rows of this lane's 8 A-tile rows
 };
 
@@ -554,17 +553,14 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     h.n0 = tm.nt * BN_OUT;
     h.widx = a.w_base;
     h.ccol = a.c_col0;
-    h.ccol2 = a.c2_col0;
     if (h.valid) {
       h.widx = a.grp_offset ? s_widx[group] : a.w_base + group;
       h.ccol = group_col0(a, group);
-      h.ccol2 = a.c2_col0 + group * a.c2_group_cols;
     } else if (fallback) {
       h.m0 = fallback->m0; h.rows = fallback->rows; h.row_base = fallback->row_base;
-      h.n0 = fallback->n0; h.widx = fallback->widx; h.ccol = fallback->ccol; h.ccol2 = fallback->ccol2;
+      h.n0 = fallback->n0; h.widx = fallback->widx; h.ccol = fallback->ccol;
     }
     h.ccol = __builtin_amdgcn_readfirstlane(h.ccol);
-    h.ccol2 = __builtin_amdgcn_readfirstlane(h.ccol2);
     h.widx = __builtin_amdgcn_readfirstlane(h.widx);
     h.m0 = __builtin_amdgcn_readfirstlane(h.m0);
     h.rows = __builtin_amdgcn_readfirstlane(h.rows);
@@ -787,8 +783,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       char* wr = stg + srow * 128 + (lane >> 5) * 8;
       const int wsw = (srow >> 1) & 7;
       const int rrow = lane >> 3, rch = lane & 7;
-      auto stage_chunk = [&](int c) {
-        char* buf = wr + (c & 1) * 4096;
+      // A chunk sequence number cc alternates the two staging buffers (cc & 1).  Without SAVE chunk cc is
+      // output chunk cc.  With SAVE the sequence is, per row block mi: the activated chunk, then the gate
+      // and the up pre-activations of the same rows (kind 0, 1, 2), so that a row block's accumulators are
+      // dead after its three chunks (keeping all of them live through a second pass spills registers, and
+      // every reload of a spilled register waits for the next tile's loads as well).
+      auto stage = [&](int cc) {
+        char* buf = wr + (cc & 1) * 4096;
+        const int kind = SAVE ? cc % 3 : 0;
+        const int c = SAVE ? cc / 3 : cc;
         const int mi = SWIGLU ? c : (c >> 1), h = SWIGLU ? 0 : (c & 1);
 #pragma unroll
         for (int nn = 0; nn < 2; ++nn)
@@ -797,8 +800,10 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
             float v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              if (SWIGLU)
+              if (SWIGLU && kind == 0)
                 v[e] = swiglu_fast(acc[2 * nn][mi][q * 4 + e], acc[2 * nn + 1][mi][q * 4 + e]);
+              else if (SWIGLU)
+                v[e] = acc[2 * nn + (kind - 1)][mi][q * 4 + e];   // kind 1: gate, 2: up
               else
                 v[e] = acc[2 * h + nn][mi][q * 4 + e];
             }
@@ -820,91 +825,61 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
           (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c_tile);
       const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
           reinterpret_cast<void*>(c_tile_u), 0, __builtin_amdgcn_readfirstlane((int)n_rec), 0x00020000);
+      // SAVE: the pre-activations go to rows of 2 * ldc elements, [gate | up] with the up half N columns
+      // further.  One descriptor spans both halves of the wave tile's valid rows; an invalid row lies past
+      // it because a row of that output is longer than N + 64 columns (2 * ldc >= 2 * N, N >= 64).
+      const int ldc2 = 2 * a.ldc;
+      const unsigned n_rec2 = SAVE && rows_left > 0 ? (unsigned)((rows_left - 1) * ldc2 + a.N + W_COLS) * 2u : 0u;
+      const unsigned long long c2_tile = reinterpret_cast<unsigned long long>(
+          static_cast<__bf16*>(SAVE ? a.C2 : a.C) + (long long)(hd.row_base + hd.m0 + wm * 128) * ldc2 + 2 * hd.ccol + col_w);
+      const unsigned long long c2_tile_u =
+          ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c2_tile >> 32)) << 32) |
+          (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c2_tile);
+      const __amdgpu_buffer_rsrc_t c2_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+          reinterpret_cast<void*>(c2_tile_u), 0, __builtin_amdgcn_readfirstlane((int)n_rec2), 0x00020000);
       u32x4 sv[4];
-      auto read_chunk = [&](int c) {
-        const char* buf = stg + (c & 1) * 4096;
+      auto read_chunk = [&](int cc) {
+        const char* buf = stg + (cc & 1) * 4096;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const int rl = it * 8 + rrow;   // row inside the 32-row chunk
           sv[it] = *reinterpret_cast<const u32x4*>(buf + rl * 128 + ((rch ^ ((rl >> 1) & 7)) * 16));
         }
       };
-      auto store_chunk = [&](int c) {
+      auto store = [&](int cc) {
+        const int kind = SAVE ? cc % 3 : 0;
+        const int c = SAVE ? cc / 3 : cc;
         const int mi = SWIGLU ? c : (c >> 1), h = SWIGLU ? 0 : (c & 1);
         const int col = h * 64 + rch * 8;   // inside the wave tile
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const int row = mi * 32 + it * 8 + rrow;
-          const unsigned off = col_w + col < a.N ? (unsigned)(row * a.ldc + col) * 2u : n_rec;
-          __builtin_amdgcn_raw_buffer_store_b128(sv[it], c_rsrc, (int)off, 0, 0);
-        }
-      };
-      // chunk c is converted and staged while the LDS reads of chunk c-1 are in flight
-      stage_chunk(0);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int c = 1; c < NCH; ++c) {
-        read_chunk(c - 1);
-        __builtin_amdgcn_sched_barrier(0);
-        stage_chunk(c);
-        __builtin_amdgcn_sched_barrier(0);
-        store_chunk(c - 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      read_chunk(NCH - 1);
-      store_chunk(NCH - 1);
-      __builtin_amdgcn_sched_barrier(0);
-      if (SAVE) {
-        // The pre-activations for a training step's backward pass: 8 more chunks (row block, gate or up) of
-        // 32 rows x 64 columns through the same two buffers, to rows of [gate | up] (the up half c2_up
-        // columns further).  One descriptor spans both halves of the wave tile's valid rows; an invalid row
-        // lies past it because a row of the output is longer than c2_up + 64 columns (f >= 64).
-        const unsigned n_rec2 = rows_left > 0 ? (unsigned)((rows_left - 1) * a.ldc2 + a.c2_up + W_COLS) * 2u : 0u;
-        const unsigned long long c2_tile = reinterpret_cast<unsigned long long>(
-            static_cast<__bf16*>(a.C2) + (long long)(hd.row_base + hd.m0 + wm * 128) * a.ldc2 + hd.ccol2 + col_w);
-        const unsigned long long c2_tile_u =
-            ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c2_tile >> 32)) << 32) |
-            (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c2_tile);
-        const __amdgpu_buffer_rsrc_t c2_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            reinterpret_cast<void*>(c2_tile_u), 0, __builtin_amdgcn_readfirstlane((int)n_rec2), 0x00020000);
-        auto stage_pre = [&](int c) {
-          char* buf = wr + (c & 1) * 4096;
-          const int mi = c >> 1, hh = c & 1;   // hh: 0 gate, 1 up
-#pragma unroll
-          for (int nn = 0; nn < 2; ++nn)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              uint2 pk;
-              pk.x = pack_bf16(acc[2 * nn + hh][mi][q * 4 + 0], acc[2 * nn + hh][mi][q * 4 + 1]);
-              pk.y = pack_bf16(acc[2 * nn + hh][mi][q * 4 + 2], acc[2 * nn + hh][mi][q * 4 + 3]);
-              *reinterpret_cast<uint2*>(buf + (((nn * 4 + q) ^ wsw) * 16)) = pk;
-            }
-        };
-        auto store_pre = [&](int c) {
-          const int mi = c >> 1, hh = c & 1;
-          const int col = rch * 8;   // inside the wave tile's 64 output columns
-#pragma unroll
-          for (int it = 0; it < 4; ++it) {
-            const int row = mi * 32 + it * 8 + rrow;
-            const unsigned off = col_w + col < a.N ? (unsigned)(row * a.ldc2 + col + hh * a.c2_up) * 2u : n_rec2;
+          if (kind == 0) {
+            const unsigned off = col_w + col < a.N ? (unsigned)(row * a.ldc + col) * 2u : n_rec;
+            __builtin_amdgcn_raw_buffer_store_b128(sv[it], c_rsrc, (int)off, 0, 0);
+          } else {
+            const unsigned off =
+                col_w + col < a.N ? (unsigned)(row * ldc2 + col + (kind - 1) * a.N) * 2u : n_rec2;
             __builtin_amdgcn_raw_buffer_store_b128(sv[it], c2_rsrc, (int)off, 0, 0);
           }
-        };
-        stage_pre(0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int c = 1; c < 8; ++c) {
-          read_chunk(c - 1);
-          __builtin_amdgcn_sched_barrier(0);
-          stage_pre(c);
-          __builtin_amdgcn_sched_barrier(0);
-          store_pre(c - 1);
-          __builtin_amdgcn_sched_barrier(0);
         }
-        read_chunk(7);
-        store_pre(7);
+      };
+      // chunk cc is converted and staged while the LDS reads of chunk cc-1 are in flight
+      constexpr int NSEQ = SAVE ? 3 * NCH : NCH;
+      stage(0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int cc = 1; cc < NSEQ; ++cc) {
+        read_chunk(cc - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        stage(cc);
+        __builtin_amdgcn_sched_barrier(0);
+        store(cc - 1);
         __builtin_amdgcn_sched_barrier(0);
       }
+      read_chunk(NSEQ - 1);
+      store(NSEQ - 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
     if (!hn.valid) break;   // uniform over the block
     hd = hn;
@@ -1142,11 +1117,11 @@ int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total
   if (swiglu && a.C2 != nullptr && !fused_save) {
     // the other kernels do not store pre-activations: two more products without the activation
     GemmArgs p = a;
-    p.C = a.C2; p.ldc = a.ldc2; p.c_group_cols = a.c2_group_cols; p.C2 = nullptr; p.B2 = nullptr; p.Bp = nullptr;
-    p.c_col0 = a.c2_col0;
+    p.C = a.C2; p.ldc = 2 * a.ldc; p.c_group_cols = 2 * a.c_group_cols; p.C2 = nullptr; p.B2 = nullptr; p.Bp = nullptr;
+    p.c_col0 = 2 * a.c_col0;
     rc = launch_gemm_main(c, p, false, total_rows, s, &fused_save);
     if (rc) return rc;
-    p.B = a.B2; p.c_col0 = a.c2_col0 + a.c2_up;
+    p.B = a.B2; p.c_col0 = 2 * a.c_col0 + a.N;
     rc = launch_gemm_main(c, p, false, total_rows, s, &fused_save);
   }
   return rc;
@@ -1219,7 +1194,7 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
       a1.B = weights->w_gate; a1.B2 = weights->w_up;
       a1.b_group_stride = (long long)c.f * c.d; a1.ldb = c.d; a1.kseg = c.d;
       a1.C = h_shared; a1.ldc = c.S * c.f; a1.c_col0 = 0; a1.c_group_cols = c.f;
-      a1.C2 = gu_shared; a1.ldc2 = c.S * 2 * c.f; a1.c2_col0 = 0; a1.c2_group_cols = 2 * c.f; a1.c2_up = c.f;
+      a1.C2 = gu_shared;   // rows of S * 2f: per shared expert [gate | up]
       a1.grp_offset = nullptr; a1.grp_widx = nullptr; a1.w_base = c.E;
       a1.ngroups = c.S; a1.M = c.T; a1.N = c.f; a1.K = c.d; a1.a_rows_total = c.T;
       const int r1 = launch_gemm(c, a1, true, c.T * c.S, s_shared);
@@ -1251,7 +1226,7 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
       g1.b_group_stride = (long long)c.f * c.d; g1.ldb = c.d; g1.kseg = c.d;
       g1.Bp = packed; g1.bp_group_stride = 4ll * c.f * c.d;
       g1.C = epd_h; g1.ldc = c.f; g1.c_col0 = 0;
-      g1.C2 = epd_gu; g1.ldc2 = 2 * c.f; g1.c2_col0 = 0; g1.c2_group_cols = 0; g1.c2_up = c.f;
+      g1.C2 = epd_gu;      // rows of 2f: [gate | up]
       g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.w_base = 0;
       g1.ngroups = c.E; g1.M = 0; g1.N = c.f; g1.K = c.d;
       g1.a_rows_total = sfd_rows_max(c);

@@ -21,9 +21,9 @@ struct GemmArgs {
   int ldc;                  // elements between C rows
   int c_col0;               // first output column written by group 0
   int c_group_cols;         // group g writes from column c_col0 + g * c_group_cols
-  void* C2;                 // SWIGLU only, or NULL: the two pre-activations are stored as well, row r of group g =
-  int ldc2;                 //   [gate | up] at columns c2_col0 + g * c2_group_cols (+ c2_up for the up half)
-  int c2_col0, c2_group_cols, c2_up;
+  void* C2;                 // SWIGLU only, or NULL: the two pre-activations are stored as well, in rows of 2 * ldc
+                            // elements: [gate | up] of group g from column 2 * (c_col0 + g * c_group_cols), the up
+                            // half N columns after the gate half
   const int32_t* grp_offset;  // [ngroups+1] logical-row prefix per group, or NULL: every group takes rows [0, M)
   const int32_t* grp_widx;    // [ngroups] weight matrix of each group, or NULL: w_base + group
   int w_base;
