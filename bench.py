@@ -34,8 +34,8 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0).  prefill: the gate/up GEMM; decode: the five
 # kernels of occult_expert_ffn together (its roofline is on all weight bytes).  Absent = not measured.
 MEASURED_TRAFFIC = {
-    "prefill_bf16": (1059894 * 2.0 + 262144) * 1024,
-    "decode_bf16": ((328328 + 169851 + 24688 + 17040 + 4108) * 2.0 + (1418 + 2048 + 1408 + 8192 + 512)) * 1024,
+    "prefill_bf16": (1069668 * 2.0 + 262144) * 1024,
+    "decode_bf16": ((328335 + 169865 + 24684 + 17038 + 4108) * 2.0 + (1418 + 2048 + 1408 + 8192 + 512)) * 1024,
 }
 
 
