@@ -296,23 +296,43 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the clamped loads past the end, before the block's LDS is released
   }
 
-  // accumulator element e of lane l: output row (e / 4) * 8 + (l / 32) * 4 + e % 4, column l % 32 of its 32 x 32 tile
+  // accumulator element e of lane l: output row (e / 4) * 8 + (l / 32) * 4 + e % 4, column l % 32 of its 32 x 32 tile.
+  // Stores (and, when accumulating, loads) go through a buffer descriptor over the wave tile's valid rows: rows
+  // past M lie beyond its range and are dropped by the hardware, columns past N are sent there: no branches.
   const int frow = lane & 31, fk = lane >> 5;
-  float* cmat = a.C + widx * a.c_mat_stride;
+  const int rows_left = min(a.M - (m0 + wm * 128), 128);
+  const int cols_left = min(a.N - (n0 + wn * 128), 128);
+  const unsigned n_rec = rows_left > 0 && cols_left > 0 ? (unsigned)((rows_left - 1) * a.ldc + cols_left) * 4u : 0u;
+  const unsigned long long c_tile = reinterpret_cast<unsigned long long>(
+      a.C + widx * a.c_mat_stride + (long long)(m0 + wm * 128) * a.ldc + n0 + wn * 128);
+  const unsigned long long c_tile_u =   // the descriptor has to sit in scalar registers
+      ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c_tile >> 32)) << 32) |
+      (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c_tile);
+  const __amdgpu_buffer_rsrc_t c_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      reinterpret_cast<void*>(c_tile_u), 0, __builtin_amdgcn_readfirstlane((int)n_rec), 0x00020000);
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 4; ++ni) {
-      const int n = n0 + wn * 128 + ni * 32 + frow;
+      const int nl = ni * 32 + frow;
+      unsigned off[16];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm * 128 + mi * 32 + (e >> 2) * 8 + fk * 4 + (e & 3);
-        if (m < a.M && n < a.N) {
-          float* p = cmat + (long long)m * a.ldc + n;
-          float v = acc[mi][ni][e];
-          if (a.accumulate) v += *p;
-          *p = v;
-        }
+        const int ml = mi * 32 + (e >> 2) * 8 + fk * 4 + (e & 3);
+        off[e] = nl < cols_left ? (unsigned)(ml * a.ldc + nl) * 4u : n_rec;
+      }
+      if (a.accumulate) {   // block-uniform; the 16 loads of a tile are in flight together
+        float old[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          old[e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(c_rsrc, (int)off[e], 0, 0));
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[mi][ni][e] += old[e];
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float v = acc[mi][ni][e];   // (a bit cast applied to the vector element itself stores element 0 sixteen times)
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), c_rsrc, (int)off[e], 0, 0);
       }
     }
 }
