@@ -817,7 +817,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       // group's end (and columns past N) are dropped by the hardware's range check: no branches.
       const int rows_left = min(hd.rows - hd.m0 - wm * 128, 128);
       const int col_w = hd.n0 + wn * W_COLS;   // first output column of the wave tile
-      const unsigned n_rec = rows_left > 0 ? (unsigned)((rows_left - 1) * a.ldc + W_COLS) * 2u : 0u;
+      // (the last valid row counts only the wave tile's columns below N: with N < W_COLS and ldc = N a
+      // whole tile width would reach into the next group's first row)
+      const int cols_left = min(a.N - col_w, W_COLS);
+      const unsigned n_rec =
+          rows_left > 0 && cols_left > 0 ? (unsigned)((rows_left - 1) * a.ldc + cols_left) * 2u : 0u;
       const unsigned long long c_tile = reinterpret_cast<unsigned long long>(
           C + (long long)(hd.row_base + hd.m0 + wm * 128) * a.ldc + hd.ccol + col_w);
       const unsigned long long c_tile_u =   // the descriptor has to sit in scalar registers
@@ -829,7 +833,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       // further.  One descriptor spans both halves of the wave tile's valid rows; an invalid row lies past
       // it because a row of that output is longer than N + 64 columns (2 * ldc >= 2 * N, N >= 64).
       const int ldc2 = 2 * a.ldc;
-      const unsigned n_rec2 = SAVE && rows_left > 0 ? (unsigned)((rows_left - 1) * ldc2 + a.N + W_COLS) * 2u : 0u;
+      const unsigned n_rec2 =
+          SAVE && rows_left > 0 && cols_left > 0 ? (unsigned)((rows_left - 1) * ldc2 + a.N + cols_left) * 2u : 0u;
       const unsigned long long c2_tile = reinterpret_cast<unsigned long long>(
           static_cast<__bf16*>(SAVE ? a.C2 : a.C) + (long long)(hd.row_base + hd.m0 + wm * 128) * ldc2 + 2 * hd.ccol + col_w);
       const unsigned long long c2_tile_u =

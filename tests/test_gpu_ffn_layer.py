@@ -43,6 +43,10 @@ SMALL = [
     ("bf16_big_shared", 1100, 192, 128, 4, 3, 1, 4, "bf16"),
     # hidden rows of 14 KiB (two column chunks in combine), long K in the first product
     ("bf16_wide_rows", 200, 7168, 128, 32, 1, 4, 8, "bf16"),
+    # outputs narrower than a wave tile of the 256-row kernel (d = 64 forward, f = 64 backward): the store
+    # range must end inside the group's last row
+    ("bf16_narrow_d", 900, 64, 128, 8, 0, 3, 2, "bf16"),
+    ("bf16_narrow_f", 1100, 192, 64, 8, 0, 3, 1, "bf16"),
 ]
 
 
