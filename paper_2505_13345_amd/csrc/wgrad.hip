@@ -233,9 +233,13 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
       for (int s = 0; s < 4; ++s) issue_idx(s);          // one ring of indices
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a wave reads only its own indices: no barrier
     }
+    // The prologue issues in the order the loop continues: indices of step NST go into the slot step 0 has just
+    // been read from (its reads have returned: the tile loads' addresses depend on them), BEFORE the tiles of
+    // steps 1 and 2, so that the constant count below covers them when step 1 reads them.
+    issue(0);
+    if (GATHER) issue_idx(NST);
 #pragma unroll
-    for (int s = 0; s < NST - 1; ++s) issue(s);
-    if (GATHER) issue_idx(NST);                          // into the slot step 0 has just been read from
+    for (int s = 1; s < NST - 1; ++s) issue(s);
     // Loads complete in order.  Per step a wave issues [indices of step s + NST + 1,] 8 tile loads of step
     // s + NST - 1.  The tiles of step s are older than the (NST - 2) * OPS loads of the last NST - 2 steps;
     // the indices used (step s + NST - 1, issued first two steps ago) are older than all but one of them.

@@ -122,6 +122,9 @@ SMALL = [
     # range must end inside the group's last row
     ("bf16_narrow_d", 900, 64, 128, 8, 0, 3, 2, "bf16"),
     ("bf16_narrow_f", 1100, 192, 64, 8, 0, 3, 1, "bf16"),
+    # many experts with 160 rows or more and short hidden rows: the gathered weight-gradient product reads the
+    # row indices of its fifth step while the loads issued before them are still in flight
+    ("bf16_gather_steps", 2300, 576, 704, 64, 0, 4, 16, "bf16"),
 ]
 
 
@@ -178,7 +181,7 @@ def _sampled_backward(name, n_sample=128):
     _check("dx (sampled)", dx[tokens], g_x, "bf16")
     _check("dw (sampled)", dw[tokens], g_w, "bf16")
     assert np.isfinite(dx).all() and np.isfinite(dw).all()
-    _check_weight_grads_on_stored_operands(layer, shape, wk.x, dy, sorted({0, shape.E // 2, shape.E - 1}))
+    _check_weight_grads_on_stored_operands(layer, shape, wk.x, dy, sorted(set(range(0, shape.E, max(1, shape.E // 8))) | {shape.E - 1}))
 
 
 def test_decode_config_backward():
