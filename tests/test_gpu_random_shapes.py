@@ -57,6 +57,11 @@ def test_random_layer_forward_and_backward(seed):
         assert mx <= 2e-2 and mean <= 2e-3, (mx, mean)
     else:
         assert f32_rel_error(y, y_ref) <= 1e-5
+    if dtype == "bf16" and not train and layer.pack_weights(wg, wu, wd) is not None:
+        # the repacked weights feed the same arithmetic: the same bits out, whichever kernel each product takes
+        layer.expert_ffn(x, wg, wu, wd)
+        layer.combine()
+        assert np.array_equal(layer.y.float().cpu().numpy(), y)
 
     dy = np.random.default_rng(seed).standard_normal((T, d)).astype(np.float32)
     if dtype == "bf16":
@@ -85,3 +90,7 @@ def test_random_layer_forward_and_backward(seed):
     else:
         assert max(errs.values()) <= 2e-6, errs
         assert f32_rel_error(dx.float().cpu().numpy(), res["g_x"]) <= 2e-5
+    # accumulate = 1 adds the same products again: exactly twice the first result
+    first = [g.clone() for g in grads]
+    for got, one in zip(layer.expert_ffn_backward_weights(x, dy_d, accumulate=True), first):
+        assert torch.equal(got, 2 * one)
