@@ -99,3 +99,26 @@ def test_router_at_config_sizes(name):
         margin = routing.selection_margin(ref, shape.k)
         assert np.all(margin[differ] <= 2 * gap + 2 * err)
     assert differ.mean() <= 1e-3
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_router_random_shapes(seed):
+    """Seeded draws over T, d (multiples of 128 for bf16), any E, D, k and pruning setting."""
+    rng = np.random.default_rng(7000 + seed)
+    dtype = "f32" if seed % 4 == 3 else "bf16"
+    E = int(rng.choice([2, 3, 5, 8, 16, 24, 60, 64, 100, 128, 200, 256]))
+    D = int(rng.choice([j for j in range(1, 65) if E % j == 0]))
+    k = int(rng.integers(1, min(E, 8) + 1))
+    T = int(rng.choice([1, 31, 32, 33, 100, 257, 1000, 3001]))
+    d = int(rng.choice([128, 256, 384, 1152, 4096])) if dtype == "bf16" else int(rng.choice([4, 37, 128, 500]))
+    mode = int(rng.integers(1, 3))
+    n_d = int(rng.integers(0, D + 1))
+    if n_d and n_d * (E // D) < k:
+        n_d = 0
+    say(f"router draw {seed}: T={T} d={d} E={E} D={D} k={k} n_d={n_d} mode={mode} {dtype}")
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    wr = (rng.standard_normal((E, d)) / np.sqrt(d)).astype(np.float32)
+    if dtype == "bf16":
+        x, wr = wl.round_to_bf16(x), wl.round_to_bf16(wr)
+    pos = wl.random_placement(E, D, seed=seed) if seed % 2 else None
+    _check(x, wr, E, D, k, dtype, n_d, mode, int(rng.integers(0, 2)), pos)
