@@ -35,10 +35,13 @@ def _check(name, got, want, dtype):
         assert mx <= 8e-2 and mean <= 4e-3, name
 
 
-def _check_weight_grads_on_stored_operands(layer, shape, x_np, dy_np, positions):
+def _check_weight_grads_on_stored_operands(layer, shape, x_np, dy_np, positions, x_dev=None, dy_dev=None):
     """The three products of occult_expert_ffn_backward_weights written out on the library's own
     stored operands (each of them compared with the oracle elsewhere in this file), in float64:
-    pins the kernel's own arithmetic (f32 accumulation over an expert's rows) tightly."""
+    pins the kernel's own arithmetic (f32 accumulation over an expert's rows) tightly.  Bar: 1e-5 of the
+    matrix's scale up to 10^4 rows; beyond, the rounding of n sequential f32 additions grows like
+    eps * sqrt(n) relative to the sum's own size, and the maximum over 10^7 elements sits ~5 deviations out:
+    1e-7 * sqrt(rows)."""
     tabs = layer.tables()
     exp_off = tabs["exp_offset"].cpu().numpy()
     pos_expert = tabs["pos_expert"].cpu().numpy()
@@ -56,16 +59,19 @@ def _check_weight_grads_on_stored_operands(layer, shape, x_np, dy_np, positions)
             if q1 == q0:
                 assert not got.any(), (name, P)
             else:
-                assert f32_rel_error(got, want.cpu().numpy()) <= 1e-5, (name, P)
-    xs = torch.from_numpy(x_np).to(layer.device).double()
-    dys = torch.from_numpy(dy_np).to(layer.device).double()
+                assert f32_rel_error(got, want.cpu().numpy()) <= max(1e-5, 1e-7 * np.sqrt(q1 - q0)), (name, P)
+    if shape.S == 0:
+        return
+    xs = (torch.from_numpy(x_np).to(layer.device) if x_dev is None else x_dev).double()
+    dys = (torch.from_numpy(dy_np).to(layer.device) if dy_dev is None else dy_dev).double()
     for sidx in range(shape.S):
         e = shape.E + sidx
         gu = layer.gu_shared[:, sidx * 2 * f:(sidx + 1) * 2 * f].double()
         want = dys.T @ layer.h_shared[:, sidx * f:(sidx + 1) * f].double()
-        assert f32_rel_error(layer.dw_down[e].cpu().numpy(), want.cpu().numpy()) <= 1e-5
-        assert f32_rel_error(layer.dw_gate[e].cpu().numpy(), (gu[:, :f].T @ xs).cpu().numpy()) <= 1e-5
-        assert f32_rel_error(layer.dw_up[e].cpu().numpy(), (gu[:, f:].T @ xs).cpu().numpy()) <= 1e-5
+        bar = max(1e-5, 1e-7 * np.sqrt(xs.shape[0]))
+        assert f32_rel_error(layer.dw_down[e].cpu().numpy(), want.cpu().numpy()) <= bar
+        assert f32_rel_error(layer.dw_gate[e].cpu().numpy(), (gu[:, :f].T @ xs).cpu().numpy()) <= bar
+        assert f32_rel_error(layer.dw_up[e].cpu().numpy(), (gu[:, f:].T @ xs).cpu().numpy()) <= bar
 
 
 def _check_per_matrix(name, got, want, dtype):
