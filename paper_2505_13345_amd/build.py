@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import concurrent.futures
 import os
+import re
 import shutil
 import subprocess
 import sys
@@ -26,6 +27,8 @@ HIPCC_FLAGS = [
     # packed-fp32 instruction forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
+    # per-kernel register and scratch figures, checked below
+    "-Rpass-analysis=kernel-resource-usage",
     "-I" + os.path.join(ROOT, "include"),
 ]
 
@@ -37,16 +40,43 @@ def _hipcc() -> str:
     return exe
 
 
+# Kernels that must not touch scratch memory: in the persistent 256-row GEMM every reload of a spilled
+# register waits for all outstanding loads, the next tile's prefetch included (a one-register change in
+# its epilogue has cost 20 % before).  Matched against the mangled kernel names.
+NO_SCRATCH = ("t256",)
+
+
+def _resource_usage(stderr: str):
+    """(kernel name, scratch bytes per lane) from the compiler's resource remarks, and the other lines."""
+    usage, rest, name = [], [], None
+    for line in stderr.splitlines():
+        if "-Rpass-analysis=kernel-resource-usage" in line:
+            text = line.split("remark:", 1)[1].strip()
+            if text.startswith("Function Name:"):
+                name = text.split(":", 1)[1].split()[0]
+            elif text.startswith("ScratchSize") and name:
+                usage.append((name, int(text.split(":")[1].split()[0])))
+            continue
+        rest.append(line)
+    # the remark's source excerpt (the kernel's signature line and a caret) follows each remark
+    rest = [l for l in rest if not re.match(r"^\s*\d*\s*\|", l)]
+    return usage, rest
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{res.stdout}\n{res.stderr}")
+    usage, rest = _resource_usage(res.stderr)
     noise = "packed-fp32-ops"
-    warn = "\n".join(l for l in res.stderr.splitlines() if noise not in l and l.strip())
+    warn = "\n".join(l for l in rest if noise not in l and l.strip() and "warning generated" not in l)
     if warn:
         sys.stderr.write(f"[{src}]\n{warn}\n")
+    spilled = [(n, b) for n, b in usage if b > 0 and any(tag in n for tag in NO_SCRATCH)]
+    if spilled:
+        raise RuntimeError(f"{src}: kernels that must stay in registers use scratch memory: {spilled}")
     return obj
 
 

@@ -819,7 +819,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       const int col_w = hd.n0 + wn * W_COLS;   // first output column of the wave tile
       // (the last valid row counts only the wave tile's columns below N: with N < W_COLS and ldc = N a
       // whole tile width would reach into the next group's first row)
-      const int cols_left = min(a.N - col_w, W_COLS);
+      // With the fused activation a wave tile is 64 columns and N a multiple of 64 (host), so a wave tile is whole
+      // or wholly past N (every store of it redirected below): the constant keeps a scalar register free there.
+      const int cols_left = SWIGLU ? W_COLS : min(a.N - col_w, W_COLS);
       const unsigned n_rec =
           rows_left > 0 && cols_left > 0 ? (unsigned)((rows_left - 1) * a.ldc + cols_left) * 2u : 0u;
       const unsigned long long c_tile = reinterpret_cast<unsigned long long>(
@@ -1046,7 +1048,7 @@ static int launch_gemm_main(const occult_cfg_t& c, const GemmArgs& a, bool swigl
     // faster on the 256-row tiles from about 64 rows per expert)
     const long long big_rows = a.grp_offset == nullptr ? 192 : (swiglu ? 129 : 64);
     const bool use_big = (long long)total_rows >= big_rows * groups && a.ksplit <= 1 &&
-                         (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK;
+                         (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK && a.N % 64 == 0;
     const bool fused_save = swiglu && a.C2 != nullptr && use_big;   // only the 256-row tiles store them themselves
     *fused_save_out = fused_save;
     // groups averaging under 24 rows: weight streaming, one wave per 32 columns x 32 tokens
