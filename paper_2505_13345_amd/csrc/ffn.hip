@@ -16,6 +16,8 @@
 #include "common.h"
 #include "gemm.h"
 
+#include <type_traits>
+
 namespace occult {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -458,6 +460,10 @@ __device__ __forceinline__ void load_to_lds_16(const char* base, unsigned off, u
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(off), "s"(base)
                : "memory", "m0");
 }
+// the same from one 64-bit address per lane
+__device__ __forceinline__ void load_to_lds_16(const char* src, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(src) : "memory", "m0");
+}
 // every load of this wave has landed and its LDS reads have returned; then the same for the block
 __device__ __forceinline__ void wait_all_and_barrier() {
   asm volatile("s_waitcnt vmcnt(0)\n\ts_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -508,9 +514,13 @@ __device__ __forceinline__ void locate(const GemmArgs& a, const int* s_goff, con
 }
 
 
-template <bool SWIGLU, bool SAVE>   // SAVE (with SWIGLU): the gate and up pre-activations are stored too (a.C2)
+// SAVE (with SWIGLU): the gate and up pre-activations are stored too (a.C2).
+// WIDE: the A operand is 4 GiB or larger, so its per-lane byte offsets take 64 bits (two registers per load
+// and a 64-bit add before each) instead of one 32-bit offset beside a scalar base.
+template <bool SWIGLU, bool SAVE, bool WIDE = false>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   static_assert(SWIGLU || !SAVE, "pre-activations exist only with the fused activation");
+  using aoff_t = typename std::conditional<WIDE, unsigned long long, unsigned>::type;
   __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
   __shared__ int s_goff[OCCULT_MAX_E + 1];   // group row offsets
   __shared__ int s_widx[OCCULT_MAX_E];       // weight matrix of each group
@@ -580,12 +590,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   };
   // loader role: load i (0..7) of this wave fills tile rows (wave*8 + i)*8 .. +7 of A and of B;
   // lane -> row lane/8, slot lane%8
-  auto offsets_of = [&](const Head& h, unsigned (&ao)[8], unsigned (&bo)[8]) {
+  auto offsets_of = [&](const Head& h, aoff_t (&ao)[8], unsigned (&bo)[8]) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int r = (wave * 8 + i) * 8 + (lane >> 3);
       const int chunk = (lane & 7) ^ ((r >> 1) & 7);
-      ao[i] = ((unsigned)h.raw[i] * (unsigned)a.lda + chunk * 8) * 2;   // host: A bytes < 2^32
+      ao[i] = ((aoff_t)(unsigned)h.raw[i] * (aoff_t)(unsigned)a.lda + chunk * 8) * 2;   // host: A bytes < 2^32 unless WIDE
       int ncol;
       if (SWIGLU) {
         const int half = r >> 7, q = (r & 127) >> 5, within = r & 31;
@@ -613,7 +623,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     foff[kk] = (lane & 31) * 128 + (((2 * kk + (lane >> 5)) ^ ((lane >> 1) & 7)) * 16);
   const int nk = a.K / BK;   // host: >= 2
 
-  unsigned a_off[8], b_off[8];
+  aoff_t a_off[8];
+  unsigned b_off[8];
   offsets_of(hd, a_off, b_off);
   const char* w_lo = static_cast<const char*>(a.B) + (long long)hd.widx * a.b_group_stride * 2;   // loads 0..3
   const char* w_hi = SWIGLU ? static_cast<const char*>(a.B2) + (long long)hd.widx * a.b_group_stride * 2 : w_lo;
@@ -629,8 +640,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       fb[set][idx - 4] = *reinterpret_cast<const bf16x8*>(Bs + (idx - 4) * 32 * 128 + foff[kk]);
   };
   // A rows / B rows of a K tile: load g (0..7) of this wave into `stage`
-  auto load_a = [&](const unsigned (&ao)[8], int ktile, int stage, int g) {
-    load_to_lds_16(a_base + (long long)ktile * (BK * 2), ao[g], lds_w + stage * STAGE_BYTES + g * 1024);
+  auto load_a = [&](const aoff_t (&ao)[8], int ktile, int stage, int g) {
+    if constexpr (WIDE)
+      load_to_lds_16(a_base + (long long)ktile * (BK * 2) + ao[g], lds_w + stage * STAGE_BYTES + g * 1024);
+    else
+      load_to_lds_16(a_base + (long long)ktile * (BK * 2), ao[g], lds_w + stage * STAGE_BYTES + g * 1024);
   };
   auto load_b = [&](const unsigned (&bo)[8], const char* lo, const char* hi, long long kb, int stage, int g) {
     load_to_lds_16((g < 4 ? lo : hi) + kb, bo[g], lds_w + stage * STAGE_BYTES + A_BYTES + g * 1024);
@@ -739,7 +753,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
     const int s = (par + nk - 2) & 1, s1 = s ^ 1;
     steps_12(s, b_off, w_lo, w_hi, kb_next);
     wait_all_and_barrier();
-    unsigned na_off[8], nb_off[8];
+    aoff_t na_off[8];
+    unsigned nb_off[8];
     offsets_of(hn, na_off, nb_off);   // the gather has long landed: nothing is outstanding here
     const char* nw_lo = static_cast<const char*>(a.B) + (long long)hn.widx * a.b_group_stride * 2;
     const char* nw_hi = SWIGLU ? static_cast<const char*>(a.B2) + (long long)hn.widx * a.b_group_stride * 2 : nw_lo;
@@ -1041,15 +1056,17 @@ static int launch_gemm_main(const occult_cfg_t& c, const GemmArgs& a, bool swigl
   *fused_save_out = false;
   if (c.dtype == OCCULT_BF16) {
     const int groups = a.ngroups;
-    // 256-row tiles once groups average enough rows, every A byte offset fits 32 bits and there
-    // are at least two K tiles to pipeline
+    // 256-row tiles once groups average enough rows and there are at least two K tiles to pipeline
+    // (an A operand of 4 GiB or more takes the variant with 64-bit row offsets)
     // (measured on 60 experts, d = 2048, f = 1408: the gate/up product is weight-bound on the
     // 128-row tiles until an expert's rows no longer fit one of them; the down projection is
     // faster on the 256-row tiles from about 64 rows per expert)
     const long long big_rows = a.grp_offset == nullptr ? 192 : (swiglu ? 129 : 64);
-    const bool use_big = (long long)total_rows >= big_rows * groups && a.ksplit <= 1 &&
-                         (long long)a.a_rows_total * a.lda * 2 < (1ll << 32) && a.K >= 2 * t256::BK && a.N % 64 == 0;
-    const bool fused_save = swiglu && a.C2 != nullptr && use_big;   // only the 256-row tiles store them themselves
+    const bool use_big =
+        (long long)total_rows >= big_rows * groups && a.ksplit <= 1 && a.K >= 2 * t256::BK && a.N % 64 == 0;
+    const bool wide = (long long)a.a_rows_total * a.lda * 2 >= (1ll << 32);
+    // only the 256-row tiles store the pre-activations themselves (not built with 64-bit offsets: registers)
+    const bool fused_save = swiglu && a.C2 != nullptr && use_big && !wide;
     *fused_save_out = fused_save;
     // groups averaging under 24 rows: weight streaming, one wave per 32 columns x 32 tokens
     const bool use_skinny = !use_big && (long long)total_rows < 24ll * groups && a.N % skinny::BN_OUT == 0;
@@ -1091,7 +1108,9 @@ static int launch_gemm_main(const occult_cfg_t& c, const GemmArgs& a, bool swigl
     const dim3 grid((unsigned)blocks, split ? (unsigned)b.ksplit : 1u), block(256);
     if (use_big) {
       if (swiglu && fused_save) hipLaunchKernelGGL((t256::grouped_gemm_bf16<true, true>), grid, block, 0, s, b);
+      else if (swiglu && wide) hipLaunchKernelGGL((t256::grouped_gemm_bf16<true, false, true>), grid, block, 0, s, b);
       else if (swiglu) hipLaunchKernelGGL((t256::grouped_gemm_bf16<true, false>), grid, block, 0, s, b);
+      else if (wide) hipLaunchKernelGGL((t256::grouped_gemm_bf16<false, false, true>), grid, block, 0, s, b);
       else hipLaunchKernelGGL((t256::grouped_gemm_bf16<false, false>), grid, block, 0, s, b);
     } else {
       if (swiglu) hipLaunchKernelGGL(small::grouped_gemm_bf16<true>, grid, block, 0, s, b);
