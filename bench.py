@@ -34,8 +34,8 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0).  prefill: the gate/up GEMM; decode: the five
 # kernels of occult_expert_ffn together (its roofline is on all weight bytes).  Absent = not measured.
 MEASURED_TRAFFIC = {
-    "prefill_bf16": (1069668 * 2.0 + 262144) * 1024,
-    "decode_bf16": ((328335 + 169865 + 24684 + 17038 + 4108) * 2.0 + (1418 + 2048 + 1408 + 8192 + 512)) * 1024,
+    "prefill_bf16": (1065006 * 2.0 + 262144) * 1024,
+    "decode_bf16": ((328340 + 169874 + 24688 + 17038 + 4113) * 2.0 + (1418 + 2048 + 1408 + 8192 + 512)) * 1024,
 }
 
 
@@ -247,7 +247,7 @@ def main():
         dom["kernel"] = "skinny::grouped_gemm_bf16 (weight streaming, both projections of occult_expert_ffn)"
     else:
         dom = dict(rooflines["ffn_gemm1_swiglu"])
-        dom["kernel"] = "t256::grouped_gemm_bf16<true, false> (gate/up projections of occult_expert_ffn)"
+        dom["kernel"] = "t256::grouped_gemm_bf16<true, false, false> (gate/up projections of occult_expert_ffn)"
     dom["traffic"] = MEASURED_TRAFFIC.get(args.workload)
 
     # backward pass (not part of the step, which is the paper's inference metric: reported beside it)
