@@ -141,3 +141,29 @@ def test_backward_and_packing_entry_points_validate_on_the_host(lib):
     odd = B.make_cfg(**dict(good, d=72))
     w = B.occult_weights_t(1 << 20, 1 << 20, 1 << 20)     # never dereferenced: the shape check comes first
     assert lib.occult_pack_weights(ctypes.byref(odd), ctypes.byref(w), 1 << 20, 1 << 30, None) == -2
+
+
+@pytest.mark.parametrize("E,seed", [(2, 0), (5, 1), (16, 2), (60, 3), (128, 4), (256, 5)])
+def test_host_similarity_table_equals_oracle(E, seed):
+    """The host table builder on random Gram matrices, with tied similarities (a zero-norm column is refused:
+    checked with the configuration errors above)."""
+    rng = np.random.default_rng(seed)
+    prof = rng.standard_normal((400, E))
+    if E >= 5:
+        prof[:, 3] = prof[:, 1]          # identical columns: equal similarities to everyone else -> index order
+    g = routing.gram(prof.astype(np.float32))
+    tab = B.occult_similarity_table(g)
+    assert tab.shape == (E, E - 1)
+    assert np.array_equal(tab, routing.similarity_table(g))
+    for i in range(E):                   # every row lists every other expert exactly once
+        assert sorted(tab[i].tolist()) == [j for j in range(E) if j != i]
+    # placement with more random shapes, including zero co-activation
+    if E % 4 == 0 and E >= 8:
+        C = rng.integers(0, 50, (E, E))
+        C = (C + C.T).astype(np.int32)
+        L, pos = B.occult_placement_greedy(C, 4)
+        L_ref, pos_ref = collaboration.greedy_placement(C.astype(np.int64), 4)
+        assert L.tolist() == L_ref and pos.tolist() == pos_ref.tolist()
+        L, pos = B.occult_placement_greedy(np.zeros((E, E), dtype=np.int32), 4)
+        L_ref, pos_ref = collaboration.greedy_placement(np.zeros((E, E), dtype=np.int64), 4)
+        assert L.tolist() == L_ref and pos.tolist() == pos_ref.tolist()
