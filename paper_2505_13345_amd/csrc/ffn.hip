@@ -116,8 +116,8 @@ constexpr int LDS_STRIDE = BK + 8;   // 144-byte rows: 16-byte reads of 8 consec
 
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
-  __shared__ __attribute__((aligned(16))) __bf16 As[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) __bf16 Bs[BN * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) __bf16 As[2][BM * LDS_STRIDE];   // two K tiles: one multiplied, one being written
+  __shared__ __attribute__((aligned(16))) __bf16 Bs[2][BN * LDS_STRIDE];
   __shared__ TileInfo s_info;
 
   constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
@@ -175,7 +175,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
   const int split = a.ksplit > 1 ? a.ksplit : 1;
   const int kt_begin = (int)((long long)blockIdx.y * nk_all / split);   // this block's K tiles
   const int nk = (int)((long long)(blockIdx.y + 1) * nk_all / split);   // (end, exclusive)
-  // two K tiles are in flight in registers while a third is multiplied out of LDS
+  // A block is alone on its CU more often than not (few tiles), so nothing else hides its own latencies: the
+  // K loop is software-pipelined.  While K tile kt is multiplied out of one LDS buffer, tile kt+1 (already in
+  // registers) is written to the other, tile kt+2 is in flight into the second register set and tile kt+3 is
+  // requested as soon as a set is free; inside a tile the fragments of K step kk+1 are read while step kk is
+  // multiplied; one barrier per tile.
   u32x4 ga0[4], gb0[4], ga1[4], gb1[4];
   auto load_global = [&](int kt, u32x4 (&ga)[4], u32x4 (&gb)[4]) {
     const int k0 = kt * BK;
@@ -187,38 +191,50 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       gb[i] = *reinterpret_cast<const u32x4*>(b_src[i] + boff);
     }
   };
-  auto k_tile = [&](int kt, u32x4 (&ga)[4], u32x4 (&gb)[4]) {
+  auto write_lds = [&](int buf, const u32x4 (&ga)[4], const u32x4 (&gb)[4]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int r = r_in + 32 * i;
-      *reinterpret_cast<u32x4*>(&As[r * LDS_STRIDE + kv * 8]) = ga[i];
-      *reinterpret_cast<u32x4*>(&Bs[r * LDS_STRIDE + kv * 8]) = gb[i];
+      *reinterpret_cast<u32x4*>(&As[buf][r * LDS_STRIDE + kv * 8]) = ga[i];
+      *reinterpret_cast<u32x4*>(&Bs[buf][r * LDS_STRIDE + kv * 8]) = gb[i];
     }
-    __syncthreads();
-    if (kt + 2 < nk) load_global(kt + 2, ga, gb);
+  };
+  bf16x8 fa[2][2], fb[2][2];
+  auto read_frags = [&](int buf, int kk, bf16x8 (&xa)[2], bf16x8 (&xb)[2]) {
+    const int kof = kk * 16 + (lane >> 5) * 8;
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+      xa[mi] = *reinterpret_cast<const bf16x8*>(&As[buf][(wm * 64 + mi * 32 + (lane & 31)) * LDS_STRIDE + kof]);
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+      xb[ni] = *reinterpret_cast<const bf16x8*>(&Bs[buf][(wn * 64 + ni * 32 + (lane & 31)) * LDS_STRIDE + kof]);
+  };
+  // K tile kt out of LDS buffer `buf`; (ga, gb) holds tile kt+1 on entry and is refilled with tile kt+3
+  auto k_tile = [&](int kt, int buf, u32x4 (&ga)[4], u32x4 (&gb)[4]) {
+    read_frags(buf, 0, fa[0], fb[0]);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[2], fb[2];
-      const int kof = kk * 16 + (lane >> 5) * 8;
-#pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-        fa[mi] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + mi * 32 + (lane & 31)) * LDS_STRIDE + kof]);
-#pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-        fb[ni] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + ni * 32 + (lane & 31)) * LDS_STRIDE + kof]);
+      if (kk + 1 < BK / 16) read_frags(buf, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+      if (kk == 1 && kt + 1 < nk) write_lds(buf ^ 1, ga, gb);
+      if (kk == 2 && kt + 3 < nk) load_global(kt + 3, ga, gb);
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][mi], fb[kk & 1][ni], acc[mi][ni], 0, 0, 0);
     }
-    __syncthreads();
+    __syncthreads();   // tile kt+1 is in the other buffer for everyone, and nobody reads this one any more
   };
-  load_global(kt_begin, ga0, gb0);
-  if (kt_begin + 1 < nk) load_global(kt_begin + 1, ga1, gb1);
-  for (int kt = kt_begin; kt < nk; kt += 2) {
-    k_tile(kt, ga0, gb0);
-    if (kt + 1 < nk) k_tile(kt + 1, ga1, gb1);
+  if (kt_begin < nk) {
+    load_global(kt_begin, ga0, gb0);
+    if (kt_begin + 1 < nk) load_global(kt_begin + 1, ga1, gb1);
+    write_lds(0, ga0, gb0);
+    if (kt_begin + 2 < nk) load_global(kt_begin + 2, ga0, gb0);
+    __syncthreads();
+    for (int kt = kt_begin; kt < nk; kt += 2) {
+      k_tile(kt, 0, ga1, gb1);
+      if (kt + 1 < nk) k_tile(kt + 1, 1, ga0, gb0);
+    }
   }
 
   // epilogue.  Accumulator element r of lane l sits at row (r/4)*8 + (l/32)*4 + r%4, column l%32.
