@@ -34,8 +34,8 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 # FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0).  prefill: the gate/up GEMM; decode: the five
 # kernels of occult_expert_ffn together (its roofline is on all weight bytes).  Absent = not measured.
 MEASURED_TRAFFIC = {
-    "prefill_bf16": (1065006 * 2.0 + 262144) * 1024,
-    "decode_bf16": ((328340 + 169874 + 24688 + 17038 + 4113) * 2.0 + (1418 + 2048 + 1408 + 8192 + 512)) * 1024,
+    "prefill_bf16": (1068305 * 2.0 + 262144) * 1024,
+    "decode_bf16": ((328340 + 169871 + 24685 + 17037 + 4113) * 2.0 + (1419 + 2048 + 1408 + 8192 + 512)) * 1024,
 }
 
 
