@@ -108,7 +108,8 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
     tile = blockIdx.x % tiles;
   }
   if (group >= a.ngroups) return;   // whole block; before any barrier
-  const int m0 = (tile / nt_n) * BM, n0 = (tile % nt_n) * BN;
+  // (the division runs in vector registers; the tile origin feeds scalar operands of the loads below)
+  const int m0 = __builtin_amdgcn_readfirstlane((tile / nt_n) * BM), n0 = __builtin_amdgcn_readfirstlane((tile % nt_n) * BN);
   int r0 = 0, r1 = a.R;
   if (a.grp_offset) {
     r0 = a.grp_offset[group];
