@@ -350,6 +350,17 @@ int occult_coactivation(const occult_cfg_t* cfg, const int32_t* ids, int32_t* C,
 int occult_placement_greedy(const int32_t* C_host, int32_t E, int32_t D, int32_t* L_host,
                             int32_t* expert_pos_host);
 
+/* Collaboration statistics of a placement (paper Sec. 3.2; the "Intra / Inter" row of Table 1), host,
+ * pure.  C_host [E][E] i32 co-activation counts (diagonal ignored), expert_pos_host [E] placement
+ * positions (NULL = contiguous), host ptrs; needs E % D == 0.  With P = C / (largest off-diagonal
+ * count), L_a = the G experts of device a:
+ *   c_intra_host[a]        = mean of P[i][j] over the G*(G-1) ordered pairs i != j inside L_a (0 if G == 1)
+ *   c_inter_host[a*D + b]  = mean of P[i][j] over the G*G pairs i in L_a, j in L_b, a != b (diagonal = 0)
+ *   *intra_fraction_host   = share of the off-diagonal mass of C whose two experts sit on one device
+ *                            (the "Intra" figure; "Inter" = 1 - it); 0 when C has no off-diagonal mass. */
+int occult_collaboration_stats(const int32_t* C_host, int32_t E, int32_t D, const int32_t* expert_pos_host,
+                               double* c_intra_host, double* c_inter_host, double* intra_fraction_host);
+
 /* Copy the plan counters to the host and derive the statistics.  Synchronises `stream`
  * (the only call that does). */
 int occult_plan_stats(const occult_cfg_t* cfg, const occult_plan_t* plan, occult_stats_t* out_host,

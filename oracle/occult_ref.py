@@ -55,21 +55,22 @@ def placement_lists(expert_pos: np.ndarray, D: int) -> List[List[int]]:
 
 
 # ------------------------------------------------------------------ BRIM_0 (Appendix A.2)
+def _running_index(present: list) -> list:
+    """Row-major numbering of the True cells of a list of rows: the n-th True cell (counting from
+    0 across rows, left to right) gets n, every False cell gets -1."""
+    flat = [c for row in present for c in row]
+    seen = np.cumsum(flat)
+    width = len(present[0]) if present else 0
+    return [[int(seen[r * width + c]) - 1 if flat[r * width + c] else -1 for c in range(width)]
+            for r in range(len(present))]
+
+
 def build_brim_0_loops(ids: np.ndarray, L: List[List[int]]) -> np.ndarray:
-    """The double loop as printed: device-major, one running counter."""
-    T = ids.shape[0]
-    D = len(L)
-    brim_0 = np.empty((D, T), dtype=np.int64)
-    ctr = 0
-    for d in range(D):
-        on_d = set(L[d])
-        for t in range(T):
-            if any(int(e) in on_d for e in ids[t]):
-                brim_0[d, t] = ctr
-                ctr += 1
-            else:
-                brim_0[d, t] = -1
-    return brim_0
+    """Pure-Python twin: the (device x token) membership table, then its row-major numbering
+    (device-major, token-ascending, one count across all devices)."""
+    present = [[bool(set(int(e) for e in ids[t]) & set(L[d])) for t in range(ids.shape[0])]
+               for d in range(len(L))]
+    return np.asarray(_running_index(present), dtype=np.int64).reshape(len(L), ids.shape[0])
 
 
 def build_brim_0(ids: np.ndarray, L: List[List[int]]) -> np.ndarray:
@@ -104,19 +105,18 @@ def dispatch(x, ids, w, brim_0):
 
 # ------------------------------------------------------------------ BRIM_1 (Appendix A.2)
 def build_brim_1_loops(ids_sfd: np.ndarray, w_sfd: np.ndarray, L_loc: List[int]):
-    n_sfd = ids_sfd.shape[0]
-    brim_1 = np.empty((len(L_loc), n_sfd), dtype=np.int64)
+    """Pure-Python twin: the (local expert x SFD row) membership table, its row-major numbering
+    (local-expert-major), and beside it the routing weight of the matching slot."""
+    n_sfd, k = ids_sfd.shape
+    slot = [[next((s for s in range(k) if int(ids_sfd[t, s]) == expert), None) for t in range(n_sfd)]
+            for expert in L_loc]
+    brim_1 = np.asarray(_running_index([[s is not None for s in row] for row in slot]),
+                        dtype=np.int64).reshape(len(L_loc), n_sfd)
     brim_w = np.zeros((len(L_loc), n_sfd), dtype=np.float64)
-    ctr = 0
-    for e in range(len(L_loc)):
-        for t in range(n_sfd):
-            hit = [s for s in range(ids_sfd.shape[1]) if int(ids_sfd[t, s]) == L_loc[e]]
-            if hit:
-                brim_1[e, t] = ctr
-                brim_w[e, t] = w_sfd[t, hit[0]]
-                ctr += 1
-            else:
-                brim_1[e, t] = -1
+    for e, row in enumerate(slot):
+        for t, s in enumerate(row):
+            if s is not None:
+                brim_w[e, t] = w_sfd[t, s]
     return brim_1, brim_w
 
 

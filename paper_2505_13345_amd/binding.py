@@ -26,6 +26,7 @@ EXPORTS = [
     "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
     "occult_transpose_weights", "occult_expert_ffn_backward", "occult_expert_ffn_backward_weights",
     "occult_pack_weights_bytes", "occult_pack_weights", "occult_expert_ffn_packed", "occult_expert_ffn_train",
+    "occult_collaboration_stats",
 ]
 
 
@@ -108,6 +109,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_expert_ffn_backward_weights.argtypes = [cfgp, planp] + [c_void_p] * 11 + [c_int, c_void_p]
     lib.occult_coactivation.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_placement_greedy.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
+    lib.occult_collaboration_stats.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_plan_stats.argtypes = [cfgp, planp, POINTER(occult_stats_t), c_void_p]
     for name in EXPORTS:
         if name not in ("occult_version", "occult_last_error"):
@@ -317,6 +319,22 @@ def occult_placement_greedy(C_host, D: int):
     pos = np.zeros(E, dtype=np.int32)
     _check(load_library().occult_placement_greedy(C_host.ctypes.data, E, D, L.ctypes.data, pos.ctypes.data))
     return L, pos
+
+
+def occult_collaboration_stats(C_host, D: int, expert_pos_host=None):
+    """C_host: numpy int32 [E, E]; expert_pos_host: numpy int32 [E] or None (contiguous).
+    Returns (c_intra [D], c_inter [D, D], intra_fraction) as computed by the library on the host."""
+    import numpy as np
+    C_host = np.ascontiguousarray(C_host, dtype=np.int32)
+    E = C_host.shape[0]
+    pos = None if expert_pos_host is None else np.ascontiguousarray(expert_pos_host, dtype=np.int32)
+    c_intra = np.zeros(max(D, 1), dtype=np.float64)
+    c_inter = np.zeros((max(D, 1), max(D, 1)), dtype=np.float64)
+    frac = c_double(0.0)
+    _check(load_library().occult_collaboration_stats(C_host.ctypes.data, E, D, None if pos is None else pos.ctypes.data,
+                                                     c_intra.ctypes.data, c_inter.ctypes.data,
+                                                     ctypes.addressof(frac)))
+    return c_intra, c_inter, float(frac.value)
 
 
 def occult_plan_stats(cfg, plan, stream=None) -> occult_stats_t:

@@ -7,6 +7,7 @@
 // result does not depend on scheduling.  E > 128 counts straight into global memory.
 #include "common.h"
 
+#include <algorithm>
 #include <vector>
 
 namespace occult {
@@ -82,6 +83,9 @@ extern "C" int occult_coactivation(const occult_cfg_t* cfg, const int32_t* ids, 
 
 // Host: greedy partition of the experts into D groups of G (Algorithm 1).  Candidates of one
 // step share their divisor, so integer sums of C are compared; the diagonal never takes part.
+// Two running score vectors replace the per-step sums over lists: to_placed[e] = summed count
+// between e and every expert placed so far, to_device[e] = the same for the device being filled;
+// a push adds one row of C to each (O(E^2) in total).
 extern "C" int occult_placement_greedy(const int32_t* C_host, int32_t E, int32_t D, int32_t* L_host,
                                        int32_t* expert_pos_host) {
   OCC_REQUIRE(C_host && L_host && expert_pos_host, OCCULT_ENULLPTR, "a pointer is NULL");
@@ -90,49 +94,82 @@ extern "C" int occult_placement_greedy(const int32_t* C_host, int32_t E, int32_t
   OCC_REQUIRE(E % D == 0, OCCULT_ESHAPE, "E=%d is not divisible by D=%d", E, D);
   const int G = E / D;
   OCC_REQUIRE(G >= 2, OCCULT_ESHAPE, "placement needs at least 2 experts per device (E/D=%d)", G);
-  auto at = [&](int i, int j) -> int64_t { return (int64_t)C_host[(size_t)i * E + j]; };
-  std::vector<char> used(E, 0);
-  std::vector<int> placed;   // all experts placed so far, in push order
-  placed.reserve(E);
+  std::vector<int64_t> to_placed(E, 0), to_device(E, 0);
+  std::vector<char> free_expert(E, 1);
+  int next_pos = 0;
+  auto push = [&](int e) {
+    const int32_t* row = C_host + (size_t)e * E;
+    for (int j = 0; j < E; ++j) {
+      to_placed[j] += row[j];
+      to_device[j] += row[j];
+    }
+    free_expert[e] = 0;
+    L_host[next_pos] = e;
+    expert_pos_host[e] = next_pos++;
+  };
+  // best free expert under `score`; sign = +1 takes the largest, -1 the smallest; first index wins ties
+  auto pick = [&](const std::vector<int64_t>& score, int sign) {
+    int best = -1;
+    for (int e = 0; e < E; ++e)
+      if (free_expert[e] && (best < 0 || sign * score[e] > sign * score[best])) best = e;
+    return best;
+  };
   for (int dev = 0; dev < D; ++dev) {
-    int* Ld = L_host + (size_t)dev * G;
-    int len = 0;
+    std::fill(to_device.begin(), to_device.end(), 0);
     if (dev == 0) {
-      int bi = 0, bj = 1;
+      // the most co-activated pair above the diagonal, row-major scan: first maximum = smallest (i, j)
+      size_t arg = 1;
       for (int i = 0; i < E; ++i)
         for (int j = i + 1; j < E; ++j)
-          if (at(i, j) > at(bi, bj)) { bi = i; bj = j; }
-      Ld[len++] = bi; Ld[len++] = bj;
-      used[bi] = used[bj] = 1;
-      placed.push_back(bi); placed.push_back(bj);
+          if (C_host[(size_t)i * E + j] > C_host[arg]) arg = (size_t)i * E + j;
+      push((int)(arg / E));
+      push((int)(arg % E));
     } else {
-      int cand = -1;
-      int64_t cand_val = 0;
-      for (int e = 0; e < E; ++e) {
-        if (used[e]) continue;
-        int64_t v = 0;
-        for (int t : placed) v += at(t, e);
-        if (cand < 0 || v < cand_val) { cand = e; cand_val = v; }
-      }
-      Ld[len++] = cand;
-      used[cand] = 1;
-      placed.push_back(cand);
+      push(pick(to_placed, -1));
     }
-    while (len < G) {
-      int cand = -1;
-      int64_t cand_val = 0;
-      for (int e = 0; e < E; ++e) {
-        if (used[e]) continue;
-        int64_t v = 0;
-        for (int i = 0; i < len; ++i) v += at(Ld[i], e);
-        if (cand < 0 || v > cand_val) { cand = e; cand_val = v; }
-      }
-      Ld[len++] = cand;
-      used[cand] = 1;
-      placed.push_back(cand);
-    }
+    while (next_pos < (dev + 1) * G) push(pick(to_device, +1));
   }
-  for (int dev = 0; dev < D; ++dev)
-    for (int sl = 0; sl < G; ++sl) expert_pos_host[L_host[(size_t)dev * G + sl]] = dev * G + sl;
+  return OCCULT_OK;
+}
+
+// Host: the placement's collaboration statistics (Sec. 3.2) from co-activation counts.
+extern "C" int occult_collaboration_stats(const int32_t* C_host, int32_t E, int32_t D,
+                                          const int32_t* expert_pos_host, double* c_intra_host,
+                                          double* c_inter_host, double* intra_fraction_host) {
+  OCC_REQUIRE(C_host && c_intra_host && c_inter_host && intra_fraction_host, OCCULT_ENULLPTR, "a pointer is NULL");
+  OCC_REQUIRE(E >= 1 && E <= OCCULT_MAX_E && D >= 1 && D <= OCCULT_MAX_D, OCCULT_EINVAL,
+              "E=%d or D=%d out of range", E, D);
+  OCC_REQUIRE(E % D == 0, OCCULT_ESHAPE, "E=%d is not divisible by D=%d", E, D);
+  const int G = E / D;
+  std::vector<int> dev_of(E);
+  for (int e = 0; e < E; ++e) {
+    const int pos = expert_pos_host ? expert_pos_host[e] : e;
+    OCC_REQUIRE(pos >= 0 && pos < E, OCCULT_EINVAL, "expert_pos[%d]=%d out of range", e, pos);
+    dev_of[e] = pos / G;
+  }
+  // block sums of the off-diagonal counts per ordered device pair, and the largest off-diagonal count
+  std::vector<int64_t> block((size_t)D * D, 0);
+  int64_t top = 0;
+  for (int i = 0; i < E; ++i)
+    for (int j = 0; j < E; ++j) {
+      if (i == j) continue;
+      const int64_t v = C_host[(size_t)i * E + j];
+      block[(size_t)dev_of[i] * D + dev_of[j]] += v;
+      if (v > top) top = v;
+    }
+  int64_t same = 0, all = 0;
+  for (int a = 0; a < D; ++a)
+    for (int b = 0; b < D; ++b) {
+      all += block[(size_t)a * D + b];
+      if (a == b) same += block[(size_t)a * D + b];
+    }
+  *intra_fraction_host = all > 0 ? (double)same / (double)all : 0.0;
+  const double scale = top > 0 ? 1.0 / (double)top : 0.0;          // P = C / largest off-diagonal count
+  for (int a = 0; a < D; ++a) {
+    const double pairs = (double)G * (G - 1);                      // ordered pairs i != j on one device
+    c_intra_host[a] = G > 1 ? (double)block[(size_t)a * D + a] * scale / pairs : 0.0;
+    for (int b = 0; b < D; ++b)
+      c_inter_host[(size_t)a * D + b] = a == b ? 0.0 : (double)block[(size_t)a * D + b] * scale / ((double)G * G);
+  }
   return OCCULT_OK;
 }

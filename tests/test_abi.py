@@ -167,3 +167,21 @@ def test_host_similarity_table_equals_oracle(E, seed):
         L, pos = B.occult_placement_greedy(np.zeros((E, E), dtype=np.int32), 4)
         L_ref, pos_ref = collaboration.greedy_placement(np.zeros((E, E), dtype=np.int64), 4)
         assert L.tolist() == L_ref and pos.tolist() == pos_ref.tolist()
+
+
+@pytest.mark.parametrize("E,D,seed", [(4, 2, 0), (16, 4, 1), (64, 16, 2), (60, 4, 3), (8, 8, 4), (6, 1, 5)])
+def test_host_collaboration_stats_equal_the_oracle(E, D, seed):
+    """occult_collaboration_stats (Sec. 3.2 averages) against the pinned oracle, contiguous and permuted."""
+    rng = np.random.default_rng(seed)
+    A = rng.integers(0, 200, (E, E))
+    C = (A + A.T).astype(np.int32)
+    for pos in (None, wl.random_placement(E, D, seed=seed)):
+        ci, cx, frac = B.occult_collaboration_stats(C, D, pos)
+        want = collaboration.collaboration_stats(C.astype(np.int64), np.arange(E) if pos is None else pos, D)
+        assert np.allclose(ci, want["c_intra"], rtol=1e-12, atol=0)
+        assert np.allclose(cx, want["c_inter"], rtol=1e-12, atol=0)
+        assert np.isclose(frac, want["intra_fraction"], rtol=1e-12, atol=0)
+    ci, cx, frac = B.occult_collaboration_stats(np.zeros((E, E), dtype=np.int32), D)
+    assert not ci.any() and not cx.any() and frac == 0.0
+    with pytest.raises(B.OccultError):
+        B.occult_collaboration_stats(C, D + 1 if E % (D + 1) else E + 1)
