@@ -15,8 +15,9 @@
  *    void*; NULL = the default stream), allocate nothing and never synchronise;
  *    the caller owns every buffer and keeps it alive until the stream has passed the call;
  *  - arguments are checked on the host before anything is launched (shape limits below);
- *    NOT checked: router scores are finite, `ids` are in range and distinct per token,
- *    `expert_pos` is a permutation of 0..E-1;
+ *    NOT checked: `ids` are in range and distinct per token, `expert_pos` is a permutation of
+ *    0..E-1.  Router scores should be finite: occult_route reads NaN and -inf as the lowest finite
+ *    value and +inf as the highest, so its ids stay distinct and below E and its gates finite;
  *  - rows of x / sfd / epd / y must start 16-byte aligned: (d * element size) % 16 == 0 and
  *    (f * element size) % 16 == 0, base pointers 16-byte aligned.
  *

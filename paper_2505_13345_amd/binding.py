@@ -125,7 +125,27 @@ def _check(rc: int) -> None:
 
 
 def _ptr(t) -> Optional[int]:
-    return None if t is None else t.data_ptr()
+    """Device address of a tensor.  The library reads raw memory, so the tensor must be a dense
+    (contiguous) block in GPU memory: anything else would hand it a pointer it misreads."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("occult: tensor is not in GPU memory")
+    if not t.is_contiguous():
+        raise ValueError(f"occult: tensor of shape {tuple(t.shape)} is not contiguous")
+    return t.data_ptr()
+
+
+def expect(t, name: str, dtype, numel: int):
+    """Marshalling check for a caller's tensor: element type and element count the call will read or
+    write (None passes through).  Returns t."""
+    if t is None:
+        return t
+    if t.dtype != dtype:
+        raise ValueError(f"occult: {name} has dtype {t.dtype}, the call needs {dtype}")
+    if t.numel() < numel:
+        raise ValueError(f"occult: {name} has {t.numel()} elements, the call needs {numel}")
+    return t
 
 
 def _stream(stream) -> Optional[int]:

@@ -11,6 +11,7 @@
 // no contraction into FMAs) so that a CPU restatement of the same text reaches the same bits.
 #include "common.h"
 
+#include <float.h>
 #include <limits.h>
 #include <math.h>
 
@@ -105,7 +106,11 @@ __device__ __forceinline__ void route_one(const float* row, int lane, int E, int
 #pragma unroll
   for (int i = 0; i < EPL; ++i) {
     const int e = lane + 64 * i;
-    v0[i] = (e < E) ? (row[e] + 0.0f) : kNegInf;
+    // NaN and -inf scores are read as the lowest finite value and +inf as the highest: every real
+    // entry then stays above the -inf that marks taken and absent entries, so each round selects a
+    // new index below E whatever the scores hold (ids index other tables downstream), and the
+    // device sums and gates stay finite
+    v0[i] = (e < E) ? fminf(fmaxf(row[e] + 0.0f, -FLT_MAX), FLT_MAX) : kNegInf;
     v[i] = v0[i];
   }
 

@@ -50,19 +50,42 @@ class OccultLayer:
                 self.h_shared = torch.zeros((T, S * f), dtype=self.tdtype, device=dev)
                 self.y_shared = torch.zeros((T, d), dtype=self.tdtype, device=dev)
 
+    # ---- element type and size of the caller's tensors (the library sees raw pointers) --------
+    def _hidden(self, t, name, rows=None):
+        s = self.shape
+        return B.expect(t, name, self.tdtype, (s["T"] if rows is None else rows) * s["d"])
+
+    def _weights(self, w_gate, w_up, w_down):
+        s = self.shape
+        n = (s["E"] + s["S"]) * s["d"] * s["f"]
+        for t, name in ((w_gate, "w_gate"), (w_up, "w_up"), (w_down, "w_down")):
+            B.expect(t, name, self.tdtype, n)
+
+    def _routing(self, ids, w):
+        s = self.shape
+        B.expect(ids, "ids", torch.int32, s["T"] * s["k"])
+        B.expect(w, "w", torch.float32, s["T"] * s["k"])
+
     # ---- steps (each = one library call on the current stream) -------------------------------
     def route(self, logits):
+        B.expect(logits, "logits", torch.float32, self.shape["T"] * self.shape["E"])
         B.occult_route(self.cfg, logits, self.ids, self.w)
 
     def route_from_hidden(self, x, w_router, logits_out):
         """Router projection x w_router^T -> logits_out [T, E] f32, then routing, in one call."""
+        s = self.shape
+        self._hidden(x, "x")
+        B.expect(w_router, "w_router", self.tdtype, s["E"] * s["d"])
+        B.expect(logits_out, "logits_out", torch.float32, s["T"] * s["E"])
         B.occult_router(self.cfg, x, w_router, logits_out, self.ids, self.w)
 
     def make_plan(self, ids=None, w=None):
+        self._routing(ids, w)
         B.occult_plan(self.cfg, self.ids if ids is None else ids, self.w if w is None else w,
                       self.plan, self.ws)
 
     def dispatch(self, x):
+        self._hidden(x, "x")
         B.occult_dispatch(self.cfg, self.plan, x, self.sfd_x)
 
     def pack_weights(self, w_gate, w_up, w_down):
@@ -77,6 +100,8 @@ class OccultLayer:
         return self.packed
 
     def expert_ffn(self, x, w_gate, w_up, w_down, use_ws=True):
+        self._hidden(x, "x")
+        self._weights(w_gate, w_up, w_down)
         if getattr(self, "packed", None) is not None:
             B.occult_expert_ffn_packed(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.packed, self.epd_h,
                                        self.epd_y, self.h_shared, self.y_shared, self.ffn_ws if use_ws else None)
@@ -92,6 +117,8 @@ class OccultLayer:
         """expert_ffn() that also keeps the pre-activations [g | u] for expert_ffn_backward(gu_saved=True)."""
         s = self.shape
         T, k, f, S = s["T"], s["k"], s["f"], s["S"]
+        self._hidden(x, "x")
+        self._weights(w_gate, w_up, w_down)
         epd_gu = self._buf("epd_gu", (T * k, 2 * f), self.tdtype)
         gu_sh = self._buf("gu_shared", (T, S * 2 * f), self.tdtype) if S > 0 else None
         B.occult_expert_ffn_train(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, w_down, self.epd_h, self.epd_y,
@@ -99,6 +126,7 @@ class OccultLayer:
         self.gu_saved = True
 
     def combine(self, epd_y=None):
+        self._hidden(epd_y, "epd_y", self.shape["T"] * self.shape["k"])
         B.occult_combine(self.cfg, self.plan, self.epd_y if epd_y is None else epd_y, self.sfd_y,
                          self.y_shared, self.y)
 
@@ -125,6 +153,9 @@ class OccultLayer:
         sfd_dy = self._buf("sfd_dy", (self.n_sfd_max, s["d"]), self.tdtype) if want_sfd else None
         epd_dy = self._buf("epd_dy", (s["T"] * s["k"], s["d"]), self.tdtype) if want_epd else None
         dw = self._buf("dw", (s["T"], s["k"]), torch.float32) if want_dw else None
+        self._hidden(dy, "dy")
+        self._hidden(epd_y, "epd_y", s["T"] * s["k"])
+        B.expect(ids, "ids", torch.int32, s["T"] * s["k"])
         B.occult_combine_backward(self.cfg, self.plan, self.ids if ids is None else ids, dy,
                                   self.epd_y if epd_y is None else epd_y, sfd_dy, epd_dy, dw)
         return sfd_dy, epd_dy, dw
@@ -134,6 +165,8 @@ class OccultLayer:
         s = self.shape
         sfd_dx = self._buf("sfd_dx", (self.n_sfd_max, s["d"]), self.tdtype)
         dx = self._buf("dx", (s["T"], s["d"]), self.tdtype)
+        self._hidden(epd_dx, "epd_dx", s["T"] * s["k"])
+        self._hidden(dx_shared, "dx_shared")
         B.occult_dispatch_backward(self.cfg, self.plan, epd_dx, sfd_dx, dx_shared, dx)
         return sfd_dx, dx
 
@@ -143,6 +176,7 @@ class OccultLayer:
         n = s["E"] + s["S"]
         w_down_t = self._buf("w_down_t", (n, s["f"], s["d"]), self.tdtype)
         w_gu_t = self._buf("w_gu_t", (n, s["d"], 2 * s["f"]), self.tdtype)
+        self._weights(w_gate, w_up, w_down)
         B.occult_transpose_weights(self.cfg, w_gate, w_up, w_down, w_down_t, w_gu_t)
         return w_down_t, w_gu_t
 
@@ -159,6 +193,10 @@ class OccultLayer:
             gu_sh = self._buf("gu_shared", (T, S * 2 * f), self.tdtype)
             dh_sh = self._buf("dh_shared", (T, S * f), self.tdtype)
             dx_sh = self._buf("dx_shared", (T, d), self.tdtype)
+        self._hidden(x, "x")
+        self._hidden(dy, "dy")
+        self._hidden(epd_dy, "epd_dy", T * k)
+        self._weights(w_gate, w_up, None)
         if gu_saved is None:   # pre-activations kept by expert_ffn_train() since the last backward
             gu_saved = getattr(self, "gu_saved", False)
         B.occult_expert_ffn_backward(self.cfg, self.plan, self.sfd_x, x, w_gate, w_up, self.w_down_t, self.w_gu_t,
@@ -173,6 +211,8 @@ class OccultLayer:
         dw_gate = self._buf("dw_gate", (n, s["f"], s["d"]), torch.float32)
         dw_up = self._buf("dw_up", (n, s["f"], s["d"]), torch.float32)
         dw_down = self._buf("dw_down", (n, s["d"], s["f"]), torch.float32)
+        self._hidden(x, "x")
+        self._hidden(dy, "dy")
         B.occult_expert_ffn_backward_weights(self.cfg, self.plan, self.sfd_x, x, self.epd_h, self.h_shared, self.epd_dy,
                                              dy, self.epd_gu, getattr(self, "gu_shared", None), dw_gate, dw_up, dw_down,
                                              accumulate)
@@ -186,6 +226,10 @@ class OccultLayer:
         return dx, dw
 
     def route_backward(self, logits, dw, dlogits, ids=None):
+        s = self.shape
+        B.expect(logits, "logits", torch.float32, s["T"] * s["E"])
+        B.expect(dlogits, "dlogits", torch.float32, s["T"] * s["E"])
+        self._routing(ids, dw)
         B.occult_route_backward(self.cfg, logits, self.ids if ids is None else ids, dw, dlogits)
 
     def stats(self):

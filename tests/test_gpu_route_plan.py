@@ -228,3 +228,33 @@ def test_similarity_pruning_matches_oracle(E, D, k, T, n_d, renorm, placement):
     torch.cuda.synchronize()
     mask = layer.tables()["tok_devmask"].cpu().numpy().astype(np.uint64)
     assert max(bin(int(m)).count("1") for m in mask) <= n_d
+
+
+@pytest.mark.parametrize("E,D,k,n_d,mode", [(16, 4, 4, 0, 1), (64, 8, 8, 2, 1), (60, 4, 4, 2, 2), (256, 16, 8, 4, 1)])
+def test_route_non_finite_scores_give_in_range_distinct_ids(E, D, k, n_d, mode):
+    """Scores are documented as finite; NaN / -inf / +inf entries are read as the extreme finite values, so
+    the routing of such a token is still k distinct experts below E (within n_d devices under pruning),
+    the plan built from it is consistent, and the finite tokens of the batch are untouched."""
+    say(f"non-finite scores E={E} D={D} k={k} n_d={n_d} mode={mode}")
+    T = 300
+    lg = wl.random_logits(T, E, seed=E + k, scale=1.3)
+    rng = np.random.default_rng(E)
+    bad = rng.choice(T, size=60, replace=False)
+    for i, t in enumerate(bad):
+        cols = rng.choice(E, size=[1, E // 2, E - 1, E][i % 4], replace=False)
+        lg[t, cols] = [np.nan, -np.inf, np.inf][i % 3]
+        if i % 5 == 0:
+            lg[t, [15 % E, 31 % E, 47 % E]] = np.nan
+    layer, ids, w = _route_gpu(lg, k, D, E, None, n_d, mode, 1)
+    good = np.setdiff1d(np.arange(T), bad)
+    ids_ref, _ = routing.route(lg[good], k, D, None, n_d=n_d, prune_mode=mode, renorm=1)
+    assert np.array_equal(ids[good], ids_ref)
+    assert ids.min() >= 0 and ids.max() < E
+    assert all(len(set(row)) == k for row in ids.tolist())
+    assert np.isfinite(w).all()
+    if n_d:
+        assert (np.array([len(set(e // (E // D) for e in row)) for row in ids.tolist()]) <= n_d).all()
+    layer.make_plan()
+    torch.cuda.synchronize()
+    trace = occult_ref.moe_forward(np.zeros((T, 1)), ids, w.astype(np.float64), np.arange(E), D)
+    check_plan_against_trace(expand_plan(layer.tables(), T, E, D, k), trace, ids, w, None, T, E, D, k)
