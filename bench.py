@@ -7,9 +7,12 @@ One step = one pass of the whole hot path over one batch of synthetic input alre
 HBM: occult_route -> occult_plan -> occult_dispatch -> occult_expert_ffn -> occult_combine ->
 occult_coactivation, enqueued back to back on one stream with no host synchronisation (with
 --graph: captured once into a HIP graph and replayed per step).
-Prints ONE JSON line.  `value` is tokens per second of the whole step; per-call times (HIP events
-on the launching stream, separate passes after the timed region), the dispatch+FFN+combine rate,
-roofline fractions and the simulated exchange bytes per token ride along in the same line.
+Prints ONE JSON line.  `value` is tokens per second of the whole step (all six calls).  Every timed
+step also records HIP events on the launching stream around dispatch, the two products of the
+expert call and combine: `timed_region_ms`, the dispatch+FFN+combine rate and the roofline
+fractions of those kernels come from these events; `calls_ms` holds every call timed again in
+separate passes after the timed region.  The simulated exchange bytes per token and the paper's
+collaboration statistics ride along in the same line.
 
 The default workload is the prefill-shaped layer (T = 2**14 tokens, E = 64, k = 8: the shape of
 the paper's Table 1 measurement, sharded over 8 simulated devices).
@@ -29,14 +32,38 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA, published
 
-# HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs scaled by a copy kernel of known size (profiles/<workload>_hbm_traffic.txt:
-# FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0).  prefill: the gate/up GEMM; decode: the five
-# kernels of occult_expert_ffn together (its roofline is on all weight bytes).  Absent = not measured.
-MEASURED_TRAFFIC = {
-    "prefill_bf16": (1068305 * 2.0 + 262144) * 1024,
-    "decode_bf16": ((328340 + 169871 + 24685 + 17037 + 4113) * 2.0 + (1419 + 2048 + 1408 + 8192 + 512)) * 1024,
-}
+COPY_PROBE_ROW = "copy probe"
+
+
+def measured_traffic(workload, kernels):
+    """HBM bytes per launch of `kernels` (summed) from profiles/<workload>_hbm_traffic.txt, the summary of
+    two rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE; raw counter values per dispatch).
+    The same runs hold a copy kernel of known size (--copy-probe-mib N: reads N MiB, writes N MiB); its row
+    fixes what one unit of each counter is worth in bytes.  None if the file, the probe row or a kernel's
+    row is missing."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    rows, probe_mib = {}, None
+    for line in open(path):
+        if line.startswith("#"):
+            if "--copy-probe-mib" in line:
+                probe_mib = float(line.split("--copy-probe-mib")[1].split()[0])
+            continue
+        cells = [c.strip() for c in line.split("|")]
+        if len(cells) >= 5:
+            rows[cells[0]] = (float(cells[2]), float(cells[4]))      # raw FETCH_SIZE, raw WRITE_SIZE
+    probe = next((v for n, v in rows.items() if n.startswith(COPY_PROBE_ROW)), None)
+    if probe is None or probe_mib is None or probe[0] <= 0 or probe[1] <= 0:
+        return None
+    bytes_per_fetch_unit = probe_mib * (1 << 20) / probe[0]
+    bytes_per_write_unit = probe_mib * (1 << 20) / probe[1]
+    total = 0.0
+    for k in kernels:
+        if k not in rows:
+            return None
+        total += rows[k][0] * bytes_per_fetch_unit + rows[k][1] * bytes_per_write_unit
+    return total
 
 
 def _event_time_ms(fn, reps):
@@ -168,14 +195,51 @@ def main():
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         run_step = graph.replay
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    # Timed region.  With host launches every step also records HIP events on the launching stream around
+    # dispatch, the two products of the expert call (issued as its two phases) and combine, so the per-kernel
+    # durations below come from the timed steps themselves.
+    live = None
+    if args.graph:
+        for _ in range(args.warmup):
+            run_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        def step_marked(ev):
+            layer.route(logits)
+            layer.make_plan()
+            ev[0].record()
+            layer.dispatch(x)
+            ev[1].record()
+            layer.cfg.ffn_phase = 1
+            layer.expert_ffn(x, wg, wu, wd)
+            ev[2].record()
+            layer.cfg.ffn_phase = 2
+            layer.expert_ffn(x, wg, wu, wd)
+            ev[3].record()
+            layer.cfg.ffn_phase = 0
+            layer.combine()
+            ev[4].record()
+            B.occult_coactivation(layer.cfg, layer.ids, C, False)
+
+        new_marks = lambda: [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        spare = new_marks()
+        for _ in range(args.warmup):
+            step_marked(spare)
+        marks = [new_marks() for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for ev in marks:
+            step_marked(ev)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        span = lambda a, b: sum(ev[a].elapsed_time(ev[b]) for ev in marks) / len(marks)
+        live = {"dispatch": span(0, 1), "ffn_gemm1_swiglu": span(1, 2), "ffn_gemm2_down": span(2, 3),
+                "expert_ffn": span(1, 3), "combine": span(3, 4), "dispatch_ffn_combine": span(0, 4)}
     ms_per_step = dt / args.steps * 1e3
     st = layer.stats()
 
@@ -240,15 +304,28 @@ def main():
         active = int((layer.tables()["exp_count"] > 0).sum().item()) + S
         rooflines["expert_ffn_weights"] = {"bound": "hbm", "achieved": gbs(active * 3.0 * d * f * es, calls["expert_ffn"]),
                                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "active_experts": active}
+    if live is not None:
+        # the same figures from the events of the timed steps
+        for n, work, unit in (("dispatch", bytes_dispatch, gbs), ("combine", bytes_combine, gbs),
+                              ("ffn_gemm1_swiglu", flops1, tf), ("ffn_gemm2_down", flops2, tf),
+                              ("expert_ffn", flops1 + flops2, tf)):
+            rooflines[n]["achieved_separate_pass"] = rooflines[n]["achieved"]
+            rooflines[n]["achieved"] = unit(work, live[n])
+        if weight_bound:
+            rooflines["expert_ffn_weights"]["achieved"] = gbs(active * 3.0 * d * f * es, live["expert_ffn"])
     for v in rooflines.values():
         v["frac"] = v["achieved"] / v["peak"]
     if weight_bound:
         dom = dict(rooflines["expert_ffn_weights"])
         dom["kernel"] = "skinny::grouped_gemm_bf16 (weight streaming, both projections of occult_expert_ffn)"
+        dom["traffic"] = measured_traffic(args.workload, [
+            "occult::skinny::grouped_gemm_bf16<true, 2, true>", "occult::skinny::grouped_gemm_bf16<false, 2, true>",
+            "occult::small::grouped_gemm_bf16<true>", "occult::small::grouped_gemm_bf16<false>",
+            "occult::splitk_reduce_bf16"])
     else:
         dom = dict(rooflines["ffn_gemm1_swiglu"])
         dom["kernel"] = "t256::grouped_gemm_bf16<true, false, false> (gate/up projections of occult_expert_ffn)"
-    dom["traffic"] = MEASURED_TRAFFIC.get(args.workload)
+        dom["traffic"] = measured_traffic(args.workload, ["occult::t256::grouped_gemm_bf16<true, false, false>"])
 
     # backward pass (not part of the step, which is the paper's inference metric: reported beside it)
     backward = None
@@ -306,9 +383,13 @@ def main():
         del dy, dlogits
         torch.cuda.empty_cache()
 
-    three = calls["dispatch"] + calls["expert_ffn"] + calls["combine"]
+    dom["timing"] = ("HIP events around the kernel in each of the timed steps" if live is not None
+                     else "HIP events around repeated calls, after the timed region")
+    three = live["dispatch_ffn_combine"] if live is not None else calls["dispatch"] + calls["expert_ffn"] + calls["combine"]
     out = {
-        "metric": "MoE-layer tokens/sec (dispatch+FFN+combine)",
+        # `value` is the whole step (all six calls); the dispatch+FFN+combine part of the same steps is
+        # tokens_per_s_dispatch_ffn_combine
+        "metric": "MoE-layer tokens/sec (whole step: route+plan+dispatch+FFN+combine+co-activation)",
         "value": T / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -322,6 +403,7 @@ def main():
                    else "caller's layout"},
         "roofline": dom,
         "calls_ms": calls,
+        "timed_region_ms": live,
         "tokens_per_s_dispatch_ffn_combine": T / (three * 1e-3),
         "rooflines": rooflines,
         "exchange": {"c_t": st.c_t, "bytes_per_token_occult": st.bytes_occ / T,
@@ -329,6 +411,18 @@ def main():
                      "saved_fraction": 1.0 - st.bytes_occ / st.bytes_std,
                      "meta_bytes_per_token": st.bytes_meta / T},
     }
+    def collaboration(ids_dev, pos_host):
+        """Sec. 3.2 statistics of a routing under a placement: co-activation counts on the GPU, averages on the host."""
+        Cc = torch.zeros((shape.E, shape.E), dtype=torch.int32, device=dev)
+        cfgc = B.make_cfg(T, d, f, shape.E, S, k, shape.D, shape.dtype, 0, 1, shape.renorm, None)
+        B.occult_coactivation(cfgc, ids_dev, Cc, False)
+        torch.cuda.synchronize()
+        c_intra, c_inter, frac = B.occult_collaboration_stats(Cc.cpu().numpy(), shape.D, pos_host)
+        off = ~np.eye(shape.D, dtype=bool)
+        return {"intra_fraction": frac, "inter_fraction": 1.0 - frac, "c_intra_mean": float(c_intra.mean()),
+                "c_inter_mean": float(c_inter[off].mean()) if shape.D > 1 else 0.0}
+
+    out["collaboration"] = collaboration(layer.ids, None)
     if backward is not None:
         out["backward"] = backward
     # The same layer with one simulated device per expert (D = E): the standard per-expert dispatch
@@ -391,6 +485,7 @@ def main():
             "bytes_per_token_contiguous": st.bytes_occ / T, "saved_fraction_vs_contiguous": 1.0 - gst.bytes_occ / st.bytes_occ,
             "calls_ms": gc, "tokens_per_s_dispatch_ffn_combine": T / (g3 * 1e-3),
             "speedup_dispatch_plus_combine": (calls["dispatch"] + calls["combine"]) / (gc["dispatch"] + gc["combine"]),
+            "collaboration": collaboration(gr.ids, pos), "collaboration_contiguous": out["collaboration"],
         }
         layer = gr
     # Collaboration pruning (paper Sec. 3.3): the same layer without pruning, for the routing change, the bytes
@@ -404,13 +499,32 @@ def main():
         y_un = un.forward(logits, x, wg, wu, wd).float()
         torch.cuda.synchronize()
         ust = un.stats()
-        same = (ids_pruned.sort(dim=1).values == un.ids.sort(dim=1).values).all(dim=1).float().mean().item()
+        same_set = lambda a, b: (a.sort(dim=1).values == b.sort(dim=1).values).all(dim=1).float().mean().item()
+        rel_l2 = lambda a, b: ((a - b).norm() / b.norm()).item()
         out["pruning"] = {
             "n_d": shape.n_d, "prune_mode": shape.prune_mode, "c_t": st.c_t, "c_t_unpruned": ust.c_t,
             "bytes_per_token": st.bytes_occ / T, "bytes_per_token_unpruned": ust.bytes_occ / T,
-            "tokens_with_unchanged_experts": same,
-            "output_rel_l2_diff_vs_unpruned": ((y_pruned - y_un).norm() / y_un.norm()).item(),
+            "tokens_with_unchanged_experts": same_set(ids_pruned, un.ids),
+            "output_rel_l2_diff_vs_unpruned": rel_l2(y_pruned, y_un),
+            "collaboration_unpruned": collaboration(un.ids, None),
         }
+        # the other device-choice rule of Sec. 3.3 (mode 2: walk the top-k in descending score until n_d devices are
+        # met; mode 1: the n_d devices of highest summed gate score), same layer and inputs
+        other = 2 if shape.prune_mode == 1 else 1
+        alt = OccultLayer(T, d, f, shape.E, S, k, shape.D, shape.dtype, shape.n_d, other, shape.renorm, None)
+        y_alt = alt.forward(logits, x, wg, wu, wd).float()
+        torch.cuda.synchronize()
+        ast = alt.stats()
+        alt_ms = {"route": _event_time_ms(lambda: alt.route(logits), r), "dispatch": _event_time_ms(lambda: alt.dispatch(x), r),
+                  "combine": _event_time_ms(lambda: alt.combine(), r)}
+        out["pruning"][f"prune_mode_{other}"] = {
+            "c_t": ast.c_t, "bytes_per_token": ast.bytes_occ / T,
+            "tokens_with_unchanged_experts": same_set(alt.ids, un.ids),
+            "tokens_with_same_experts_as_configured_mode": same_set(alt.ids, ids_pruned),
+            "output_rel_l2_diff_vs_unpruned": rel_l2(y_alt, y_un),
+            "calls_ms": alt_ms, "collaboration": collaboration(alt.ids, None),
+        }
+        del alt, y_alt
         layer = un
     if not args.no_cpu_baseline:
         del layer

@@ -29,20 +29,51 @@ local experts in slot order, then over devices in ascending order, as in the for
 Softmax over all E experts, the values at the k selected experts, optionally divided by their sum.
 The selection itself is piecewise constant and contributes nothing.
 Float arithmetic is float64.
+
+Storage rounding (``storage=`` of `layer_backward`, `expert_ffn_backward`, `combine_backward`): the
+paper keeps parameters and activations in bfloat16 (Section 4, Experimental Setup), so a bfloat16
+implementation of this chain stores every tensor that travels between two products in that type.
+Given ``storage`` (e.g. `to_bf16`), the same float64 chain is evaluated with each such tensor passed
+through it, at the points listed in `layer_backward`; with ``storage=None`` nothing is rounded (the
+exact gradient, pinned by central differences in tests/test_oracle_backward.py).  The rounded chain
+is what a bfloat16 implementation is compared with at a tight bar: the two then differ only by
+accumulation order and by values that sit on a rounding boundary.
 """
 from __future__ import annotations
 
 import numpy as np
 
 
-def combine_backward(g_y, out_epd, brim_0, brim_1, brim_w, dev_count):
+def to_bf16(a):
+    """Nearest bfloat16 (8 significant bits, ties to even) of float32(a), as float64: the upper 16 bits of
+    the float32 pattern after adding half a step (0x7FFF, plus the lowest kept bit so that ties go to the
+    even mantissa).  Finite values below the overflow threshold only."""
+    u = np.asarray(a, dtype=np.float32).view(np.uint32)
+    u = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return u.view(np.float32).astype(np.float64)
+
+
+def to_bf16_by_mantissa(a):
+    """The same rounding from its definition, for float64 input: scale the mantissa to 8 bits, round to
+    nearest even, scale back (slow; the twin that pins `to_bf16`)."""
+    m, e = np.frexp(np.asarray(a, dtype=np.float64))      # a = m * 2**e with 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e)
+
+
+def _keep(a):
+    return a
+
+
+def combine_backward(g_y, out_epd, brim_0, brim_1, brim_w, dev_count, storage=None):
     """Transposes of "Combine" and of the weighted merge.
 
     g_y [T, d] gradient of the layer output; out_epd: per device, the experts' output rows
     [n_epd_dev, d] in the device's local EPD order; brim_0 [D, T]; brim_1 / brim_w per device.
     Returns g_sfd [N_sfd, d], per device g_out [n_epd_dev, d] and g_w [G, n_sfd_dev] (gradient of
-    brim_w; zero where BRIM_1 is -1).
+    brim_w; zero where BRIM_1 is -1).  ``storage`` rounds the rows of g_out (they are stored and read
+    again by the experts' backward).
     """
+    rnd = storage or _keep
     D, T = brim_0.shape
     n_sfd = int(np.sum(dev_count))
     g_sfd = np.zeros((n_sfd, g_y.shape[1]), dtype=np.float64)
@@ -60,7 +91,7 @@ def combine_backward(g_y, out_epd, brim_0, brim_1, brim_w, dev_count):
         for e in range(b1.shape[0]):
             v = b1[e]
             present = v >= 0
-            g_out[v[present]] = bw[e, present][:, None] * seg[present]
+            g_out[v[present]] = rnd(bw[e, present][:, None] * seg[present])
             g_w[e, present] = np.einsum("rc,rc->r", seg[present], out_epd[d][v[present]].astype(np.float64))
         g_out_all.append(g_out)
         g_w_all.append(g_w)
@@ -139,35 +170,49 @@ def route_backward(logits, ids, g_w, renorm):
     return p * (g_p - (g_p * p).sum(axis=1, keepdims=True))
 
 
-def expert_ffn_backward(v, g_out, w_gate, w_up, w_down, with_pre=False):
+def expert_ffn_backward(v, g_out, w_gate, w_up, w_down, with_pre=False, storage=None, store_g_v=True):
     """Backward of one SwiGLU expert E(v) = W_down (silu(W_gate v) * (W_up v)) for rows v [n, d] and
     output gradients g_out [n, d] (the forward is the expert of the baseline configuration; the
     chain rule through it, nothing else).  Returns g_v [n, d] and the weight gradients
     (g_w_gate [f, d], g_w_up [f, d], g_w_down [d, f]) summed over the rows; ``with_pre`` appends the
-    gradients of the two pre-activations, [g_gate | g_up] as rows of 2f."""
+    gradients of the two pre-activations, [g_gate | g_up] as rows of 2f.
+    ``storage`` rounds the tensors kept between the products: the pre-activations as the derivative
+    reads them, the intermediate h the forward pass kept (rounded from the unrounded
+    pre-activations, as the forward pass computes it), the gradient of h, the gradients of the
+    pre-activations and (unless ``store_g_v`` is False: the caller sums several experts first) the rows
+    of g_v; the weight gradients are sums in full precision of the rounded factors."""
+    rnd = storage or _keep
     v = v.astype(np.float64)
     g_out = g_out.astype(np.float64)
     wg, wu, wd = (a.astype(np.float64) for a in (w_gate, w_up, w_down))
     g = v @ wg.T
     u = v @ wu.T
+    h = rnd(g / (1.0 + np.exp(-g)) * u)                # what the forward pass stored
+    g, u = rnd(g), rnd(u)
     sig = 1.0 / (1.0 + np.exp(-g))
-    h = g * sig * u
-    g_h = g_out @ wd                                   # [n, f]
-    g_g = g_h * u * sig * (1.0 + g * (1.0 - sig))      # d silu(g) / d g = sig * (1 + g * (1 - sig))
-    g_u = g_h * g * sig
+    g_h = rnd(g_out @ wd)                              # [n, f]
+    g_g = rnd(g_h * u * sig * (1.0 + g * (1.0 - sig)))  # d silu(g) / d g = sig * (1 + g * (1 - sig))
+    g_u = rnd(g_h * g * sig)
     g_v = g_g @ wg + g_u @ wu
+    if store_g_v:
+        g_v = rnd(g_v)
     if with_pre:
         return g_v, (g_g.T @ v, g_u.T @ v, g_out.T @ h), np.concatenate([g_g, g_u], axis=1)
     return g_v, (g_g.T @ v, g_u.T @ v, g_out.T @ h)
 
 
-def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
+def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y, storage=None):
     """Backward of the whole deduplicated layer, the forward pipeline walked in reverse on the same
     re-index matrices: transposed Combine and merge, the experts' own backward per device and local
     expert, transposed row gather and Dispatch; shared experts see every token with weight 1.
     Returns a dict: g_x [T, d], g_w [T, k], g_w_gate / g_w_up / g_w_down like the weights, and the
-    intermediate payloads g_sfd_y, g_sfd_x and per-device EPD rows g_epd_y, g_epd_gu ([g_gate | g_up]), g_epd_x."""
+    intermediate payloads g_sfd_y, g_sfd_x and per-device EPD rows g_epd_y, g_epd_gu ([g_gate | g_up]), g_epd_x.
+    ``storage`` (see the module text) rounds: the forward's kept tensors (the intermediate h and the
+    experts' output rows, which the gate gradient reads), the gate-scaled output-gradient rows, every
+    tensor `expert_ffn_backward` lists, the SFD payload of the return trip, the shared experts' summed
+    input gradient, and g_x itself."""
     from . import occult_ref
+    rnd = storage or _keep
     T, d = x.shape
     E = len(expert_pos)
     tr = occult_ref.moe_forward(x, ids, w, expert_pos, D)
@@ -184,9 +229,9 @@ def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
             if present.any():
                 g = seg[present] @ w_gate[expert].astype(np.float64).T
                 u = seg[present] @ w_up[expert].astype(np.float64).T
-                rows[v[present]] = (g / (1.0 + np.exp(-g)) * u) @ w_down[expert].astype(np.float64).T
+                rows[v[present]] = rnd(rnd(g / (1.0 + np.exp(-g)) * u) @ w_down[expert].astype(np.float64).T)
         out_epd.append(rows)
-    g_sfd_y, g_out, g_bw = combine_backward(g_y, out_epd, tr.brim_0, tr.brim_1, tr.brim_w, tr.dev_count)
+    g_sfd_y, g_out, g_bw = combine_backward(g_y, out_epd, tr.brim_0, tr.brim_1, tr.brim_w, tr.dev_count, storage)
     g_wg = np.zeros(w_gate.shape)
     g_wu = np.zeros(w_up.shape)
     g_wd = np.zeros(w_down.shape)
@@ -200,7 +245,8 @@ def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
             present = v >= 0
             if present.any():
                 g_v, (a, b, c), gu = expert_ffn_backward(seg[present], g_out[j][v[present]], w_gate[expert],
-                                                         w_up[expert], w_down[expert], with_pre=True)
+                                                         w_up[expert], w_down[expert], with_pre=True,
+                                                         storage=storage)
                 rows[v[present]] = g_v
                 pre[v[present]] = gu
                 g_wg[expert] += a
@@ -208,13 +254,17 @@ def layer_backward(x, ids, w, expert_pos, D, w_gate, w_up, w_down, S, g_y):
                 g_wd[expert] += c
         g_in.append(rows)
         g_pre.append(pre)
-    g_sfd_x, g_x = dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count)
+    g_sfd_x, g_x = dispatch_backward(g_in, tr.brim_0, tr.brim_1, tr.dev_count, sfd_round=storage)
+    g_shared = np.zeros_like(g_x)
     for s in range(S):
-        g_v, (a, b, c) = expert_ffn_backward(x, g_y, w_gate[E + s], w_up[E + s], w_down[E + s])
-        g_x = g_x + g_v
+        # the shared experts' input gradients are summed before they are stored: one rounding
+        g_v, (a, b, c) = expert_ffn_backward(x, g_y, w_gate[E + s], w_up[E + s], w_down[E + s],
+                                             storage=storage, store_g_v=False)
+        g_shared += g_v
         g_wg[E + s] += a
         g_wu[E + s] += b
         g_wd[E + s] += c
+    g_x = rnd(g_x + rnd(g_shared)) if S else rnd(g_x)
     return {"g_x": g_x, "g_w": gate_grad_to_slots(g_bw, ids, tr.brim_0, L, tr.dev_count),
             "g_w_gate": g_wg, "g_w_up": g_wu, "g_w_down": g_wd, "g_sfd_y": g_sfd_y, "g_sfd_x": g_sfd_x,
             "g_epd_x": g_in, "g_epd_y": g_out, "g_epd_gu": g_pre, "trace": tr}

@@ -105,3 +105,43 @@ def f32_rel_error(got: np.ndarray, want: np.ndarray):
     rms = float(np.sqrt(np.mean(want ** 2)))
     den = np.maximum(np.abs(want), rms)
     return float((np.abs(got.astype(np.float64) - want) / den).max())
+
+
+# ---- bars derived from the storage type ------------------------------------------------------------
+# bfloat16 keeps 8 significant bits: rounding to nearest moves a value by at most half a step of 2^-7
+# relative to its leading power of two, i.e. by at most 2^-8 of the value itself.
+BF16_U = 2.0 ** -8
+
+
+def chain_mean_bar(n_roundings: int) -> float:
+    """Upper bound on (mean |error|) / rms of a result that passed through `n_roundings` stored bf16
+    tensors: each rounding adds an independent relative error of at most BF16_U, uniform inside its
+    step, hence of rms <= BF16_U / sqrt(3) of the value; independent errors add in quadrature, sums of
+    such values keep the relative figure, and a mean absolute value never exceeds the rms."""
+    return float(np.sqrt(n_roundings) * BF16_U / np.sqrt(3.0))
+
+
+def assert_one_rounding(got: np.ndarray, want: np.ndarray, what: str) -> None:
+    """`got` is `want` (float64, from the same stored operands) accumulated in f32 and rounded once to bf16:
+    every element within one rounding (BF16_U of its value) plus the f32 accumulation and fast-math error
+    (2e-5 of the tensor's rms: f32 sums of up to a few thousand products, hardware exp and reciprocal)."""
+    want = want.astype(np.float64)
+    rms = float(np.sqrt(np.mean(want ** 2)))
+    excess = np.abs(got.astype(np.float64) - want) - (BF16_U * (1 + 2.0 ** -10) * np.abs(want) + 2e-5 * rms)
+    worst = float(excess.max())
+    assert worst <= 0.0, f"{what}: an element is {worst:.3e} beyond one bf16 rounding (rms {rms:.3e})"
+
+
+_workloads = {}
+
+
+def cached_workload(shape):
+    """Workloads of the large configurations are drawn once per test session (the pruned prefill
+    configuration reads the same tensors as the unpruned one: same seed, same draw order)."""
+    from inputs import workloads as wl
+    key = (shape.T, shape.d, shape.f, shape.E, shape.S, shape.dtype, shape.components)
+    if key not in _workloads:
+        say(f"{shape.name}: generating")
+        _workloads.clear()            # one large workload at a time
+        _workloads[key] = wl.make_workload(shape)
+    return _workloads[key]

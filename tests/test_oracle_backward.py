@@ -292,3 +292,62 @@ def test_per_token_backward_equals_the_pipeline_backward():
     g_x, g_w = backward.moe_layer_backward_tokens(x, ids, w, wg, wu, wd, E, S, g_y, tokens)
     assert np.allclose(g_x, res["g_x"][tokens], rtol=1e-11, atol=1e-12)
     assert np.allclose(g_w, res["g_w"][tokens], rtol=1e-11, atol=1e-12)
+
+
+def test_to_bf16_is_round_to_nearest_even_on_eight_bits():
+    """Hand values: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> even mantissa (1); 1 + 3*2^-8 is
+    halfway between 1 + 2^-7 and 1 + 2^-6 -> even (1 + 2^-6); exactly representable values stay; the
+    error is at most half a step of 2^-7 relative to the leading power of two, so at most 2^-8 relative; and every float32 whose low 16 bits are zero is a fixed point."""
+    for r in (backward.to_bf16, backward.to_bf16_by_mantissa):
+        _bf16_pins(r)
+    a32 = (np.random.default_rng(1).standard_normal(50000) * 7).astype(np.float32).astype(np.float64)
+    assert np.array_equal(backward.to_bf16(a32), backward.to_bf16_by_mantissa(a32))
+
+
+def _bf16_pins(r):
+    assert r(1.0 + 2.0 ** -8) == 1.0 and r(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert r(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7
+    assert r(-0.3) == -0.30078125 and r(0.0) == 0.0      # -0.3 = -1.2 * 2^-2, 1.2 -> 154/128
+    rng = np.random.default_rng(0)
+    a = rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))
+    assert np.all(np.abs(r(a) - a) <= np.abs(a) * 2.0 ** -8)
+    # sign and exponent 64..191 (finite, normal), 7 mantissa bits, low 16 bits zero
+    bits = ((rng.integers(0, 2, 5000) << 15) | (rng.integers(64, 192, 5000) << 7) | rng.integers(0, 128, 5000))
+    bits = bits.astype(np.uint32) << np.uint32(16)
+    exact = bits.view(np.float32).astype(np.float64)
+    assert np.array_equal(r(exact), exact)
+    # a library's float32 -> bfloat16 conversion (round to nearest even) on float32 inputs
+    import torch
+    a32 = a.astype(np.float32)
+    lib = torch.from_numpy(a32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(r(a32.astype(np.float64)), lib)
+
+
+def test_storage_rounding_variant_brackets_the_exact_gradient():
+    """The rounded chain (i) is the exact chain when nothing is rounded, (ii) returns the exact values when
+    every stored tensor is exactly representable (small integers through identity-like experts), and
+    (iii) otherwise stays within a few roundings (2^-8 relative each) per stored tensor of the exact gradient."""
+    rng = np.random.default_rng(3)
+    T, E, S, k, D, d, f = 24, 8, 1, 3, 4, 16, 8
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    pos = rng.permutation(E).astype(np.int32)
+    ids, w = routing.route(logits, k, D, pos)
+    x = rng.standard_normal((T, d))
+    g_y = rng.standard_normal((T, d))
+    wg, wu = rng.standard_normal((E + S, f, d)) / 4, rng.standard_normal((E + S, f, d)) / 4
+    wd = rng.standard_normal((E + S, d, f)) / 4
+    exact = backward.layer_backward(x, ids, w, pos, D, wg, wu, wd, S, g_y)
+    same = backward.layer_backward(x, ids, w, pos, D, wg, wu, wd, S, g_y, storage=lambda a: a)
+    for key in ("g_x", "g_w", "g_w_gate", "g_w_up", "g_w_down", "g_sfd_x"):
+        assert np.array_equal(exact[key], same[key]), key
+    rounded = backward.layer_backward(x, ids, w, pos, D, wg, wu, wd, S, g_y, storage=backward.to_bf16)
+    for key in ("g_x", "g_w", "g_w_gate", "g_w_up", "g_w_down"):
+        rms = np.sqrt(np.mean(exact[key] ** 2))
+        err = np.abs(rounded[key] - exact[key])
+        assert 0 < err.mean() / rms < 2 * 2.0 ** -8 and err.max() / rms < 16 * 2.0 ** -8, (key, err.mean() / rms, err.max() / rms)
+    assert np.array_equal(backward.to_bf16(rounded["g_x"]), rounded["g_x"])        # g_x is itself a stored tensor
+    assert np.array_equal(backward.to_bf16(rounded["g_sfd_x"]), rounded["g_sfd_x"])
+    # one expert evaluated alone: with store_g_v=False only the last rounding is left out
+    a = backward.expert_ffn_backward(x, g_y, wg[0], wu[0], wd[0], storage=backward.to_bf16)[0]
+    b = backward.expert_ffn_backward(x, g_y, wg[0], wu[0], wd[0], storage=backward.to_bf16, store_g_v=False)[0]
+    assert np.array_equal(a, backward.to_bf16(b)) and not np.array_equal(a, b)
