@@ -177,6 +177,19 @@ int occult_router(const occult_cfg_t* cfg, const void* x, const void* w_router, 
 int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
                 const occult_plan_t* plan, void* ws, size_t ws_bytes, occult_stream_t stream);
 
+/* occult_plan for callers that cannot allocate device memory or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same three kernels with their
+ * scratch (the per-block counts) in a device array built into the library, OCCULT_PLAN_STATIC_MAX_BYTES
+ * on every GPU the library runs on, held until the process ends.  Allocates nothing and calls no
+ * allocating routine; the array's device address is looked up on the first call on each device (make
+ * that call outside a capture).  Results are bit-identical to occult_plan.  Layers whose workspace_bytes
+ * (occult_plan_sizes) exceed the limit are refused with OCCULT_EWORKSPACE before anything is launched.
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (two
+ * streams, two threads) race; the buffer's old contents never matter (each call overwrites what it reads). */
+#define OCCULT_PLAN_STATIC_MAX_BYTES (4u << 20)
+int occult_plan_static(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
+                       const occult_plan_t* plan, occult_stream_t stream);
+
 /* Dispatch ORI -> SFD (paper App. A.2 "Dispatch"): sfd_x[tok_sfd_row[t][j]] = x[t] for every
  * device j of token t.  x [T][d], sfd_x [>= N_sfd][d] (allocate T*min(k,D) rows), device ptrs. */
 int occult_dispatch(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* x, void* sfd_x,

@@ -26,7 +26,7 @@ EXPORTS = [
     "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
     "occult_transpose_weights", "occult_expert_ffn_backward", "occult_expert_ffn_backward_weights",
     "occult_pack_weights_bytes", "occult_pack_weights", "occult_expert_ffn_packed", "occult_expert_ffn_train",
-    "occult_collaboration_stats",
+    "occult_collaboration_stats", "occult_plan_static",
 ]
 
 
@@ -85,6 +85,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_similarity_table.argtypes = [c_void_p, c_int32, c_void_p]
     lib.occult_router.argtypes = [cfgp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_plan.argtypes = [cfgp, c_void_p, c_void_p, planp, c_void_p, c_size_t, c_void_p]
+    lib.occult_plan_static.argtypes = [cfgp, c_void_p, c_void_p, planp, c_void_p]
     lib.occult_dispatch.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p]
     lib.occult_dispatch_meta.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.occult_expert_ffn.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t),
@@ -213,6 +214,10 @@ def occult_router(cfg, x, w_router, logits, ids, w, stream=None) -> None:
 def occult_plan(cfg, ids, w, plan: occult_plan_t, ws, stream=None) -> None:
     _check(load_library().occult_plan(ctypes.byref(cfg), _ptr(ids), _ptr(w), ctypes.byref(plan), _ptr(ws),
                                       ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def occult_plan_static(cfg, ids, w, plan: occult_plan_t, stream=None) -> None:
+    _check(load_library().occult_plan_static(ctypes.byref(cfg), _ptr(ids), _ptr(w), ctypes.byref(plan), _stream(stream)))
 
 
 def occult_dispatch(cfg, plan, x, sfd_x, stream=None) -> None:

@@ -16,6 +16,8 @@
 // sequential counters would visit.  Every table is therefore bit-reproducible.
 #include "common.h"
 
+#include <mutex>
+
 namespace occult {
 
 constexpr int kTPB = kPlanTokensPerBlock;   // 256 threads = 4 waves, one token per thread
@@ -248,29 +250,12 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
 
 size_t plan_workspace_bytes(const occult_cfg_t& c);
 
-}  // namespace occult
-
-using namespace occult;
-
-extern "C" int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
-                           const occult_plan_t* plan, void* ws, size_t ws_bytes, occult_stream_t stream) {
-  int rc = check_cfg(cfg);
-  if (rc) return rc;
-  const occult_cfg_t c = *cfg;
-  OCC_REQUIRE(plan, OCCULT_ENULLPTR, "plan is NULL");
-  const occult_plan_t p = *plan;
-  OCC_REQUIRE(p.tok_devmask && p.dev_count && p.dev_offset && p.tok_sfd_row && p.sfd_token &&
-                  p.exp_count && p.exp_offset && p.pos_expert && p.epd_sfd_row && p.epd_gate &&
-                  p.sfd_epd_rows && p.counters,
-              OCCULT_ENULLPTR, "a plan table is NULL (use occult_plan_bind)");
-  OCC_REQUIRE(ws, OCCULT_ENULLPTR, "workspace is NULL");
-  OCC_REQUIRE(ws_bytes >= plan_workspace_bytes(c), OCCULT_EWORKSPACE, "workspace of %zu bytes < required %zu",
-              ws_bytes, plan_workspace_bytes(c));
-  OCC_REQUIRE(c.T == 0 || (ids && w), OCCULT_ENULLPTR, "ids or w is NULL");
-  hipStream_t s = static_cast<hipStream_t>(stream);
+// The three launches of the planner on a block-count buffer `blk` of >= nblk * (D + E) ints.  plan_count
+// writes every entry of the first nblk rows before plan_scan reads them: the buffer need not be cleared.
+static int launch_plan(const occult_cfg_t& c, const int32_t* ids, const float* w, const occult_plan_t& p,
+                       int32_t* blk, hipStream_t s) {
   const int G = c.E / c.D;
   const int nblk = (c.T + kTPB - 1) / kTPB;
-  int32_t* blk = static_cast<int32_t*>(ws);
   if (nblk > 0) {
     hipLaunchKernelGGL(plan_count, dim3(nblk, c.D), dim3(kTPB), 0, s, ids, c.T, c.k, c.E, c.D, G, c.expert_pos,
                        p.tok_devmask, blk);
@@ -293,4 +278,77 @@ extern "C" int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const fl
     OCC_LAUNCH_CHECK("plan_fill");
   }
   return OCCULT_OK;
+}
+
+static int check_plan_args(const occult_cfg_t& c, const int32_t* ids, const float* w, const occult_plan_t* plan) {
+  OCC_REQUIRE(plan, OCCULT_ENULLPTR, "plan is NULL");
+  const occult_plan_t& p = *plan;
+  OCC_REQUIRE(p.tok_devmask && p.dev_count && p.dev_offset && p.tok_sfd_row && p.sfd_token &&
+                  p.exp_count && p.exp_offset && p.pos_expert && p.epd_sfd_row && p.epd_gate &&
+                  p.sfd_epd_rows && p.counters,
+              OCCULT_ENULLPTR, "a plan table is NULL (use occult_plan_bind)");
+  OCC_REQUIRE(c.T == 0 || (ids && w), OCCULT_ENULLPTR, "ids or w is NULL");
+  return OCCULT_OK;
+}
+
+// Scratch of occult_plan_static: the planner's per-block counts in a device array of the library
+// itself (4 MiB on every GPU the library runs on, held until the process ends).  On the host this
+// name only stands for the array: its device address comes from hipGetSymbolAddress, once per
+// device, and is what the kernels receive.
+constexpr size_t kStaticPlanInts = (size_t)OCCULT_PLAN_STATIC_MAX_BYTES / sizeof(int32_t);
+static __device__ __align__(256) int32_t scratch[kStaticPlanInts];
+
+constexpr int kMaxHipDevices = 64;
+static std::mutex g_scratch_mutex;
+static int32_t* g_scratch_ptr[kMaxHipDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call for that device).
+static int static_scratch(int32_t** out) {
+  int dev = -1;
+  OCC_HIP(hipGetDevice(&dev));
+  OCC_REQUIRE(dev >= 0 && dev < kMaxHipDevices, OCCULT_EINVAL, "HIP device %d outside 0..%d", dev, kMaxHipDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    OCC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    OCC_REQUIRE(ptr, OCCULT_EHIP, "hipGetSymbolAddress returned a NULL address for the planner's scratch");
+    g_scratch_ptr[dev] = static_cast<int32_t*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return OCCULT_OK;
+}
+
+}  // namespace occult
+
+using namespace occult;
+
+extern "C" int occult_plan(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
+                           const occult_plan_t* plan, void* ws, size_t ws_bytes, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  rc = check_plan_args(c, ids, w, plan);
+  if (rc) return rc;
+  OCC_REQUIRE(ws, OCCULT_ENULLPTR, "workspace is NULL");
+  OCC_REQUIRE(ws_bytes >= plan_workspace_bytes(c), OCCULT_EWORKSPACE, "workspace of %zu bytes < required %zu",
+              ws_bytes, plan_workspace_bytes(c));
+  return launch_plan(c, ids, w, *plan, static_cast<int32_t*>(ws), static_cast<hipStream_t>(stream));
+}
+
+extern "C" int occult_plan_static(const occult_cfg_t* cfg, const int32_t* ids, const float* w,
+                                  const occult_plan_t* plan, occult_stream_t stream) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  const occult_cfg_t c = *cfg;
+  const size_t need = plan_workspace_bytes(c);
+  OCC_REQUIRE(need <= (size_t)OCCULT_PLAN_STATIC_MAX_BYTES, OCCULT_EWORKSPACE,
+              "this layer's planner scratch (%zu bytes for T=%d, D+E=%d) exceeds the %zu bytes of the built-in "
+              "buffer: use occult_plan with a caller workspace",
+              need, c.T, c.D + c.E, (size_t)OCCULT_PLAN_STATIC_MAX_BYTES);
+  rc = check_plan_args(c, ids, w, plan);
+  if (rc) return rc;
+  int32_t* blk = nullptr;
+  rc = static_scratch(&blk);
+  if (rc) return rc;
+  return launch_plan(c, ids, w, *plan, blk, static_cast<hipStream_t>(stream));
 }

@@ -185,3 +185,15 @@ def test_host_collaboration_stats_equal_the_oracle(E, D, seed):
     assert not ci.any() and not cx.any() and frac == 0.0
     with pytest.raises(B.OccultError):
         B.occult_collaboration_stats(C, D + 1 if E % (D + 1) else E + 1)
+
+
+def test_plan_static_refuses_layers_beyond_its_built_in_scratch(lib):
+    """The size check of occult_plan_static comes before any HIP call: a layer needing more than
+    OCCULT_PLAN_STATIC_MAX_BYTES of planner scratch gets OCCULT_EWORKSPACE and a message naming the limit."""
+    big = B.make_cfg(T=20_000_000, d=64, f=64, E=256, S=0, k=1, D=64, dtype="bf16")
+    _, ws = B.occult_plan_sizes(big)
+    assert ws > 4 << 20
+    assert lib.occult_plan_static(ctypes.byref(big), None, None, None, None) == -5
+    assert "4194304" in B.occult_last_error()
+    ok = B.make_cfg(T=4096, d=64, f=64, E=64, S=0, k=8, D=8, dtype="bf16")
+    assert lib.occult_plan_static(ctypes.byref(ok), None, None, None, None) == -4     # NULL plan, still on the host
