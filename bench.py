@@ -127,6 +127,9 @@ def main():
                     help="decode-shaped workloads: read the weights in the caller's layout instead of the repacked copy")
     ap.add_argument("--no-backward", action="store_true",
                     help="skip timing the backward calls (occult_combine_backward, occult_expert_ffn_backward, ...)")
+    ap.add_argument("--merge-atomic", action="store_true",
+                    help="also time occult_combine_atomic (the paper's atomic first-stage merge: f32 and packed bf16 atomics) "
+                         "beside occult_combine")
     ap.add_argument("--cpu-sample", type=int, default=16384)
     ap.add_argument("--call-reps", type=int, default=10)
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -426,6 +429,16 @@ def main():
                 "c_inter_mean": float(c_inter[off].mean()) if shape.D > 1 else 0.0}
 
     out["collaboration"] = collaboration(layer.ids, None)
+    if args.merge_atomic:
+        # the paper's first-stage merge through atomic adds (Sec. 3.1) against the order-fixed fused combine
+        modes = {"f32_atomics": 0, "packed_bf16_atomics": 1} if shape.dtype == "bf16" else {"f32_atomics": 0}
+        am = {n: _event_time_ms(lambda m=m: layer.combine_atomic(mode=m), r) for n, m in modes.items()}
+        out["atomic_merge"] = {"calls_ms": am, "combine_ms": calls["combine"],
+                               "merged_rows": n_epd, "target_rows": n_sfd, "payload_bytes": n_epd * row,
+                               "note": "clear + atomic merge + stage 2 (three kernels) against the fused order-fixed occult_combine"}
+        layer.combine()
+        layer.sfd_acc = None
+        torch.cuda.empty_cache()
     if backward is not None:
         out["backward"] = backward
     # The same layer with one simulated device per expert (D = E): the standard per-expert dispatch

@@ -262,6 +262,19 @@ int occult_expert_ffn_packed(const occult_cfg_t* cfg, const occult_plan_t* plan,
 int occult_combine(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_y,
                    void* sfd_y, const void* y_shared, void* y, occult_stream_t stream);
 
+/* occult_combine with the paper's own first stage, an atomic merge (paper Sec. 3.1, first-stage merging: thread
+ * blocks that write the same SFD rows add with atomic_add into a float32 output tensor that is converted to the
+ * target type afterwards; App. A.2 "SMM with Merging").  Opt-in, for measuring it beside the order-fixed default:
+ *   mode 0: every EPD row q adds epd_gate[q] * epd_y[q] into sfd_acc[epd_sfd_row[q]] with float32 atomic adds
+ *           (sfd_acc: device ptr f32 [>= N_sfd][d], allocate T*min(k,D) rows; its first N_sfd rows are cleared by
+ *           the call); then sfd_y[r] = sfd_acc[r] rounded to cfg.dtype and stage 2 exactly as occult_combine;
+ *   mode 1: (bf16 layers) the same additions as packed bf16 atomic adds straight into sfd_y (cleared by the call;
+ *           one bf16 rounding per addition; sfd_acc may be NULL); stage 2 as occult_combine.
+ * The order of the additions into a row is not fixed: results are not bit-reproducible and agree with
+ * occult_combine up to float reassociation (bit for bit when every partial sum is exactly representable). */
+int occult_combine_atomic(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* epd_y, float* sfd_acc,
+                          void* sfd_y, const void* y_shared, void* y, int mode, occult_stream_t stream);
+
 /* Backward pass of the data movement (the paper trains through the layer: Introduction, Sec. 4
  * Training; it prints no backward algorithm, and every forward step here is linear in the hidden
  * rows, so the gradient is the transposed map on the same plan, Sec. 3.1).  Both calls leave the

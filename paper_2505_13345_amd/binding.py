@@ -26,7 +26,7 @@ EXPORTS = [
     "occult_combine_backward", "occult_dispatch_backward", "occult_route_backward",
     "occult_transpose_weights", "occult_expert_ffn_backward", "occult_expert_ffn_backward_weights",
     "occult_pack_weights_bytes", "occult_pack_weights", "occult_expert_ffn_packed", "occult_expert_ffn_train",
-    "occult_collaboration_stats", "occult_plan_static",
+    "occult_collaboration_stats", "occult_plan_static", "occult_combine_atomic",
 ]
 
 
@@ -98,6 +98,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_expert_ffn_packed.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t), c_void_p,
                                              c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.occult_combine.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.occult_combine_atomic.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_combine_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                             c_void_p]
     lib.occult_dispatch_backward.argtypes = [cfgp, planp, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -277,6 +278,11 @@ def occult_expert_ffn_packed(cfg, plan, sfd_x, x, w_gate, w_up, w_down, packed, 
 def occult_combine(cfg, plan, epd_y, sfd_y, y_shared, y, stream=None) -> None:
     _check(load_library().occult_combine(ctypes.byref(cfg), ctypes.byref(plan), _ptr(epd_y), _ptr(sfd_y),
                                          _ptr(y_shared), _ptr(y), _stream(stream)))
+
+
+def occult_combine_atomic(cfg, plan, epd_y, sfd_acc, sfd_y, y_shared, y, mode=0, stream=None) -> None:
+    _check(load_library().occult_combine_atomic(ctypes.byref(cfg), ctypes.byref(plan), _ptr(epd_y), _ptr(sfd_acc), _ptr(sfd_y),
+                                                _ptr(y_shared), _ptr(y), int(mode), _stream(stream)))
 
 
 def occult_combine_backward(cfg, plan, ids, dy, epd_y, sfd_dy, epd_dy, dw, stream=None) -> None:

@@ -19,7 +19,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build", "occult")
 LIB_PATH = os.path.join(HERE, "liboccult.so")
 
-SOURCES = ["api.hip", "route.hip", "plan.hip", "dispatch.hip", "ffn.hip", "combine.hip", "coact.hip", "backward.hip",
+SOURCES = ["api.hip", "route.hip", "plan.hip", "dispatch.hip", "ffn.hip", "combine.hip", "combine_atomic.hip", "coact.hip", "backward.hip",
            "ffn_backward.hip", "wgrad.hip"]
 
 HIPCC_FLAGS = [

@@ -130,6 +130,15 @@ class OccultLayer:
         B.occult_combine(self.cfg, self.plan, self.epd_y if epd_y is None else epd_y, self.sfd_y,
                          self.y_shared, self.y)
 
+    def combine_atomic(self, epd_y=None, mode=0):
+        """combine() with the paper's atomic merge as its first stage (mode 0: float32 atomics into a scratch
+        tensor allocated on first use; mode 1: packed bf16 atomics into sfd_y)."""
+        s = self.shape
+        self._hidden(epd_y, "epd_y", s["T"] * s["k"])
+        acc = self._buf("sfd_acc", (self.n_sfd_max, s["d"]), torch.float32) if mode == 0 else None
+        B.occult_combine_atomic(self.cfg, self.plan, self.epd_y if epd_y is None else epd_y, acc, self.sfd_y,
+                                self.y_shared, self.y, mode)
+
     def forward(self, logits, x, w_gate, w_up, w_down, train=False):
         self.route(logits)
         self.make_plan()

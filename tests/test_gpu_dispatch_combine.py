@@ -68,6 +68,15 @@ def test_dispatch_and_combine_bit_exact_on_exact_inputs(E, D, k, T, d, dtype, pl
     torch.cuda.synchronize()
     assert np.array_equal(layer.sfd_y[:n_sfd].float().cpu().numpy(), trace.y_sfd)
     assert np.array_equal(layer.y.float().cpu().numpy(), trace.y)
+    # the atomic merge (paper Sec. 3.1, first-stage merging through atomic_add): with every partial sum exactly
+    # representable the order of the additions cannot matter, so both of its modes give the same bits
+    for mode in ((0, 1) if dtype == "bf16" else (0,)):
+        layer.sfd_y.fill_(7.0)
+        layer.y.fill_(7.0)
+        layer.combine_atomic(epd_y.contiguous(), mode=mode)
+        torch.cuda.synchronize()
+        assert np.array_equal(layer.sfd_y[:n_sfd].float().cpu().numpy(), trace.y_sfd), mode
+        assert np.array_equal(layer.y.float().cpu().numpy(), trace.y), mode
 
 
 @pytest.mark.parametrize("dtype,S", [("bf16", 0), ("bf16", 1), ("f32", 0), ("f32", 1)])
@@ -126,6 +135,24 @@ def test_combine_random_values_against_two_stage_oracle(dtype, S):
     else:
         assert f32_rel_error(got_sfd, sfd_ref) <= 1e-5
         assert f32_rel_error(got_y, y_ref) <= 1e-5
+    # the atomic merge against the same oracle sums (their order is the hardware's: tolerance only)
+    for mode in ((0, 1) if dtype == "bf16" else (0,)):
+        layer.sfd_y.fill_(7.0)
+        layer.y.fill_(7.0)
+        layer.combine_atomic(to_dev(epd_y, dtype, dev), mode=mode)
+        torch.cuda.synchronize()
+        a_sfd = layer.sfd_y[:n_sfd].float().cpu().numpy()
+        a_y = layer.y.float().cpu().numpy()
+        if dtype == "bf16":
+            mx, mean = bf16_errors(a_sfd, sfd_ref)
+            assert mx <= 2e-2 and mean <= 2e-3, (mode, mx, mean)
+            mx, mean = bf16_errors(a_y, y_ref)
+            assert mx <= 2e-2 and mean <= 2e-3, (mode, mx, mean)
+            if mode == 0:   # f32 sums in another order, rounded once: at most one bf16 step from the order-fixed payload
+                assert np.abs(a_sfd - got_sfd).max() <= 2.0 ** -7 * max(1.0, np.abs(sfd_ref).max())
+        else:
+            assert f32_rel_error(a_sfd, sfd_ref) <= 1e-5
+            assert f32_rel_error(a_y, y_ref) <= 1e-5
 
 
 META_CASES = [(16, 4, 4, 211, "random"), (60, 4, 4, 128, "contig"), (64, 8, 8, 4099, "random"),
