@@ -811,10 +811,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
       constexpr int NCH = SWIGLU ? 4 : 8;
       constexpr int W_COLS = SWIGLU ? 64 : 128;   // output columns of a wave tile
       const int srow = lane & 31;
-      // (the 32 lanes of one half wave write 8 bytes each to rows 0..31: rows r and r + 16 share their bank line
-      // and slot, so the rows from 16 on keep the two 8-byte halves of every 16-byte slot exchanged, and the
-      // half wave covers all 64 banks; read_chunk exchanges them back)
-      char* wr = stg + srow * 128 + (((lane >> 5) ^ (srow >> 4)) * 8);
+      char* wr = stg + srow * 128 + (lane >> 5) * 8;
       const int wsw = (srow >> 1) & 7;
       const int rrow = lane >> 3, rch = lane & 7;
       // A chunk sequence number cc alternates the two staging buffers (cc & 1).  Without SAVE chunk cc is
@@ -884,8 +881,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
           const int rl = it * 8 + rrow;   // row inside the 32-row chunk
-          const u32x4 t = *reinterpret_cast<const u32x4*>(buf + rl * 128 + ((rch ^ ((rl >> 1) & 7)) * 16));
-          sv[it] = it < 2 ? t : u32x4{t.z, t.w, t.x, t.y};   // rows 16..31: halves exchanged when staged
+          sv[it] = *reinterpret_cast<const u32x4*>(buf + rl * 128 + ((rch ^ ((rl >> 1) & 7)) * 16));
         }
       };
       auto store = [&](int cc) {
