@@ -202,7 +202,9 @@ def main():
     # dispatch, the two products of the expert call (issued as its two phases) and combine, so the per-kernel
     # durations below come from the timed steps themselves.
     live = None
-    if args.graph:
+    # decode-shaped steps (a few hundred microseconds of small kernels) are timed without the per-step events:
+    # five event records per step cost about a tenth of such a step
+    if args.graph or shape.T * shape.k < 24 * shape.E:
         for _ in range(args.warmup):
             run_step()
         torch.cuda.synchronize()
