@@ -20,6 +20,9 @@ __global__ void fill_i32(int32_t* __restrict__ p, size_t n, int32_t v) {
     p[i] = v;
 }
 
+// OVERWRITE: the launch is a single block that owns the whole result: its LDS tile is stored, not added, and C
+// needs no clearing beforehand.
+template <bool OVERWRITE>
 __global__ __launch_bounds__(kCoactThreads) void coact_lds_kernel(const int32_t* __restrict__ ids, int T,
                                                                   int k, int E, int32_t* __restrict__ C) {
   extern __shared__ int s_c[];   // [E*E]
@@ -35,7 +38,8 @@ __global__ __launch_bounds__(kCoactThreads) void coact_lds_kernel(const int32_t*
   __syncthreads();
   for (int i = threadIdx.x; i < E * E; i += kCoactThreads) {
     const int v = s_c[i];
-    if (v) atomicAdd(&C[i], v);
+    if (OVERWRITE) C[i] = v;
+    else if (v) atomicAdd(&C[i], v);
   }
 }
 
@@ -63,15 +67,19 @@ extern "C" int occult_coactivation(const occult_cfg_t* cfg, const int32_t* ids, 
   OCC_REQUIRE(c.T == 0 || ids, OCCULT_ENULLPTR, "ids is NULL");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t n = (size_t)c.E * c.E;
-  if (!accumulate) {
+  int blocks = (c.T + kCoactThreads - 1) / kCoactThreads;
+  if (blocks > 512) blocks = 512;
+  const bool single = !accumulate && blocks == 1 && c.E <= kCoactLdsMaxE;   // decode steps: one launch, no clearing
+  if (!accumulate && !single) {
     hipLaunchKernelGGL(fill_i32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, C, n, 0);
     OCC_LAUNCH_CHECK("fill_i32");
   }
   if (c.T == 0) return OCCULT_OK;
-  int blocks = (c.T + kCoactThreads - 1) / kCoactThreads;
-  if (blocks > 512) blocks = 512;
-  if (c.E <= kCoactLdsMaxE) {
-    hipLaunchKernelGGL(coact_lds_kernel, dim3(blocks), dim3(kCoactThreads), n * sizeof(int), s, ids, c.T, c.k,
+  if (single) {
+    hipLaunchKernelGGL(coact_lds_kernel<true>, dim3(1), dim3(kCoactThreads), n * sizeof(int), s, ids, c.T, c.k, c.E, C);
+    OCC_LAUNCH_CHECK("coact_lds_kernel");
+  } else if (c.E <= kCoactLdsMaxE) {
+    hipLaunchKernelGGL(coact_lds_kernel<false>, dim3(blocks), dim3(kCoactThreads), n * sizeof(int), s, ids, c.T, c.k,
                        c.E, C);
     OCC_LAUNCH_CHECK("coact_lds_kernel");
   } else {

@@ -248,6 +248,126 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
   }
 }
 
+// A batch of at most one block of tokens (T <= 256: decode steps): count, scan and fill in one launch
+// of one block.  The same ballots, popcounts and scan orders as the three kernels above, with the counts of
+// all devices and positions held in LDS instead of the block-count buffer, so every table comes out
+// bit-identical; what goes is two of three launches.
+template <int KMAX>
+__global__ __launch_bounds__(kTPB) void plan_single(
+    const int32_t* __restrict__ ids, const float* __restrict__ w, int T, int k, int E, int D, int G, int M1,
+    const int32_t* __restrict__ expert_pos, uint64_t* __restrict__ tok_devmask, int32_t* __restrict__ dev_count,
+    int32_t* __restrict__ dev_offset, int32_t* __restrict__ exp_count, int32_t* __restrict__ exp_offset,
+    int32_t* __restrict__ pos_expert, uint64_t* __restrict__ counters, int32_t* __restrict__ tok_sfd_row,
+    int32_t* __restrict__ sfd_token, int32_t* __restrict__ epd_sfd_row, float* __restrict__ epd_gate,
+    int32_t* __restrict__ sfd_epd_rows) {
+  __shared__ int s_pos[OCCULT_MAX_E];
+  __shared__ int s_cnt[kWavesPerBlock][kMaxCols];   // per-wave counts, then each wave's first rank
+  __shared__ int s_start[kMaxCols];                 // exclusive scans: devices, then positions
+  for (int e = threadIdx.x; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
+  __syncthreads();
+  const int t = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int C = D + E;
+  const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
+  int tpos[KMAX];
+  float tgate[KMAX];
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    const bool live = (t < T) && (s < k);
+    tpos[s] = live ? s_pos[ids[(size_t)t * k + s]] : -1;
+    tgate[s] = live ? w[(size_t)t * k + s] : 0.0f;
+  }
+  if (t < T) tok_devmask[t] = b.dev;
+  for (int j = 0; j < D; ++j) {
+    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
+    if (lane == 0) s_cnt[wave][j] = __popcll(m);
+    for (int sl = 0; sl < G; ++sl) {
+      const unsigned long long mp = __ballot(has_pos(b, j * G + sl));
+      if (lane == 0) s_cnt[wave][D + j * G + sl] = __popcll(mp);
+    }
+  }
+  __syncthreads();
+  // column totals (into the scan array), then the two scans over devices and over positions
+  for (int c = threadIdx.x; c < C; c += kTPB) {
+    int tot = 0;
+#pragma unroll
+    for (int wv = 0; wv < kWavesPerBlock; ++wv) tot += s_cnt[wv][c];
+    s_start[c] = tot;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0, mx = 0;
+    for (int j = 0; j < D; ++j) {
+      const int n = s_start[j];
+      s_start[j] = run;
+      dev_count[j] = n;
+      dev_offset[j] = run;
+      mx = max(mx, n);
+      run += n;
+    }
+    dev_offset[D] = run;
+    counters[0] = (uint64_t)run;
+    counters[3] = (uint64_t)mx;
+  } else if (threadIdx.x == 64) {
+    int run = 0, mx = 0;
+    for (int P = 0; P < E; ++P) {
+      const int n = s_start[D + P];
+      s_start[D + P] = run;
+      exp_count[P] = n;
+      exp_offset[P] = run;
+      mx = max(mx, n);
+      run += n;
+    }
+    exp_offset[E] = run;
+    counters[1] = (uint64_t)run;
+    counters[2] = (uint64_t)T * (uint64_t)k;
+    counters[4] = (uint64_t)mx;
+    counters[5] = counters[6] = counters[7] = 0;
+  } else if (threadIdx.x >= 128) {
+    for (int e = threadIdx.x - 128; e < E; e += kTPB - 128) pos_expert[s_pos[e]] = e;
+  }
+  __syncthreads();
+  // per-wave counts -> first rank of each wave in each column
+  for (int c = threadIdx.x; c < C; c += kTPB) {
+    int run = s_start[c];
+#pragma unroll
+    for (int wv = 0; wv < kWavesPerBlock; ++wv) {
+      const int n = s_cnt[wv][c];
+      s_cnt[wv][c] = run;
+      run += n;
+    }
+  }
+  __syncthreads();
+  const int* first = s_cnt[wave];
+  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int j = 0; j < D; ++j) {
+    const bool on = (b.dev >> j) & 1ull;
+    const unsigned long long m = __ballot(on);
+    const int r = on ? first[j] + __popcll(m & lt) : -1;
+    if (t < T) tok_sfd_row[(size_t)t * D + j] = r;
+    if (on) sfd_token[r] = t;
+    int filled = 0;   // merge-list entries of SFD row r written so far
+    for (int sl = 0; sl < G; ++sl) {
+      const int P = j * G + sl;
+      const bool hit = has_pos(b, P);
+      const unsigned long long me = __ballot(hit);
+      if (me == 0ull) continue;   // wave-uniform
+      if (hit) {
+        const int q = first[D + P] + __popcll(me & lt);
+        float gate = 0.0f;
+#pragma unroll
+        for (int s = 0; s < KMAX; ++s) gate = (tpos[s] == P) ? tgate[s] : gate;
+        epd_sfd_row[q] = r;
+        epd_gate[q] = gate;
+        sfd_epd_rows[(size_t)r * M1 + filled] = q;
+        ++filled;
+      }
+    }
+    if (on)
+      for (int i = filled; i < M1; ++i) sfd_epd_rows[(size_t)r * M1 + i] = -1;
+  }
+}
+
 size_t plan_workspace_bytes(const occult_cfg_t& c);
 
 // The three launches of the planner on a block-count buffer `blk` of >= nblk * (D + E) ints.  plan_count
@@ -256,6 +376,19 @@ static int launch_plan(const occult_cfg_t& c, const int32_t* ids, const float* w
                        int32_t* blk, hipStream_t s) {
   const int G = c.E / c.D;
   const int nblk = (c.T + kTPB - 1) / kTPB;
+  if (nblk == 1) {   // one block of tokens: the three passes in one launch (blk stays unused)
+#define OCC_PLAN_SINGLE(KM)                                                                                     \
+  hipLaunchKernelGGL(plan_single<KM>, dim3(1), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G, merge_width(c),  \
+                     c.expert_pos, p.tok_devmask, p.dev_count, p.dev_offset, p.exp_count, p.exp_offset,          \
+                     p.pos_expert, p.counters, p.tok_sfd_row, p.sfd_token, p.epd_sfd_row, p.epd_gate,            \
+                     p.sfd_epd_rows)
+    if (c.k <= 8) OCC_PLAN_SINGLE(8);
+    else if (c.k <= 16) OCC_PLAN_SINGLE(16);
+    else OCC_PLAN_SINGLE(32);
+#undef OCC_PLAN_SINGLE
+    OCC_LAUNCH_CHECK("plan_single");
+    return OCCULT_OK;
+  }
   if (nblk > 0) {
     hipLaunchKernelGGL(plan_count, dim3(nblk, c.D), dim3(kTPB), 0, s, ids, c.T, c.k, c.E, c.D, G, c.expert_pos,
                        p.tok_devmask, blk);
