@@ -354,6 +354,21 @@ int occult_expert_ffn_backward_weights(const occult_cfg_t* cfg, const occult_pla
                                        const void* gu_shared, float* dw_gate, float* dw_up, float* dw_down,
                                        int accumulate, occult_stream_t stream);
 
+/* occult_expert_ffn_backward_weights with a scratch buffer.  Shared experts are fewer than 8 groups that each take all
+ * T rows: at large T their products have far fewer workgroups (groups x 256 x 256 output tiles) than the chip has
+ * compute units.  Given `ws` (device ptr, 16-byte aligned, >= occult_expert_ffn_backward_weights_ws_bytes() bytes) the
+ * rows of such a product are cut into up to 8 slices of at least 2048 rows, every slice a workgroup of its own writing
+ * an f32 partial product to ws; a second kernel adds the slices in slice order (order-fixed, no atomics) and writes or,
+ * with accumulate = 1, adds the sum.  The sums then run in another order than without ws (same bars, other last bits).
+ * ws == NULL, too few bytes, or a layer that does not need it (ws_bytes == 0): identical to the call above.  The
+ * contents of ws are not kept between calls. */
+int occult_expert_ffn_backward_weights_ws_bytes(const occult_cfg_t* cfg, size_t* ws_bytes);
+int occult_expert_ffn_backward_weights_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                          const void* x, const void* epd_h, const void* h_shared, const void* epd_dy,
+                                          const void* dy, const void* epd_gu, const void* gu_shared, float* dw_gate,
+                                          float* dw_up, float* dw_down, int accumulate, void* ws, size_t ws_bytes,
+                                          occult_stream_t stream);
+
 /* Gradient of the routing weights with respect to the router scores (paper Eq. 1: Softmax over
  * all E experts, the values at the selected experts, divided by their sum if cfg.renorm; the
  * selection is piecewise constant and has no gradient).  logits [T][E] f32, ids [T][k] as returned

@@ -27,6 +27,7 @@ EXPORTS = [
     "occult_transpose_weights", "occult_expert_ffn_backward", "occult_expert_ffn_backward_weights",
     "occult_pack_weights_bytes", "occult_pack_weights", "occult_expert_ffn_packed", "occult_expert_ffn_train",
     "occult_collaboration_stats", "occult_plan_static", "occult_combine_atomic",
+    "occult_expert_ffn_backward_weights_ws_bytes", "occult_expert_ffn_backward_weights_ws",
 ]
 
 
@@ -109,6 +110,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.occult_expert_ffn_train.argtypes = [cfgp, planp, c_void_p, c_void_p, POINTER(occult_weights_t)] + [c_void_p] * 7 + [
         c_size_t, c_void_p]
     lib.occult_expert_ffn_backward_weights.argtypes = [cfgp, planp] + [c_void_p] * 11 + [c_int, c_void_p]
+    lib.occult_expert_ffn_backward_weights_ws_bytes.argtypes = [cfgp, POINTER(c_size_t)]
+    lib.occult_expert_ffn_backward_weights_ws.argtypes = [cfgp, planp] + [c_void_p] * 11 + [c_int, c_void_p, c_size_t, c_void_p]
     lib.occult_coactivation.argtypes = [cfgp, c_void_p, c_void_p, c_int, c_void_p]
     lib.occult_placement_greedy.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p]
     lib.occult_collaboration_stats.argtypes = [c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
@@ -331,6 +334,21 @@ def occult_expert_ffn_backward_weights(cfg, plan, sfd_x, x, epd_h, h_shared, epd
     _check(load_library().occult_expert_ffn_backward_weights(
         ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x), _ptr(epd_h), _ptr(h_shared), _ptr(epd_dy), _ptr(dy),
         _ptr(epd_gu), _ptr(gu_shared), _ptr(dw_gate), _ptr(dw_up), _ptr(dw_down), int(bool(accumulate)), _stream(stream)))
+
+
+def occult_expert_ffn_backward_weights_ws_bytes(cfg) -> int:
+    n = c_size_t(0)
+    _check(load_library().occult_expert_ffn_backward_weights_ws_bytes(ctypes.byref(cfg), ctypes.byref(n)))
+    return int(n.value)
+
+
+def occult_expert_ffn_backward_weights_ws(cfg, plan, sfd_x, x, epd_h, h_shared, epd_dy, dy, epd_gu, gu_shared, dw_gate,
+                                          dw_up, dw_down, ws, accumulate=False, stream=None) -> None:
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().occult_expert_ffn_backward_weights_ws(
+        ctypes.byref(cfg), ctypes.byref(plan), _ptr(sfd_x), _ptr(x), _ptr(epd_h), _ptr(h_shared), _ptr(epd_dy), _ptr(dy),
+        _ptr(epd_gu), _ptr(gu_shared), _ptr(dw_gate), _ptr(dw_up), _ptr(dw_down), int(bool(accumulate)), _ptr(ws), nbytes,
+        _stream(stream)))
 
 
 def occult_coactivation(cfg, ids, C, accumulate: bool = False, stream=None) -> None:

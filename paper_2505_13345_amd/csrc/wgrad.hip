@@ -35,6 +35,12 @@ struct WgradArgs {
   int w_base, ngroups, R;
   int M, N;
   int accumulate;            // 0: C = product, 1: C += product
+  int rsplit;                // uniform groups only (grp_offset == NULL): the R rows are cut into rsplit slices of
+                             // rslice rows (a multiple of the step), each a workgroup of its own that writes its f32
+                             // partial product to ws[slice][group][M][N]; wgrad_reduce adds the slices in order.
+                             // 0 or 1: no split
+  int rslice;
+  float* ws;
 };
 
 // ------------------------------------------------------------------------------------------
@@ -98,22 +104,29 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
   const int tiles = ((a.M + BM - 1) / BM) * nt_n;
   // with 8 groups or more a group's tiles share an XCD (and its L2); fewer groups (shared experts: few
   // groups of many rows) are spread over all XCDs instead
-  int group, tile;
+  int group, tile, slice = 0;
   if (a.ngroups >= 8) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     group = (slot / tiles) * 8 + xcd;
     tile = slot % tiles;
   } else {
-    group = blockIdx.x / tiles;
-    tile = blockIdx.x % tiles;
+    const int per_slice = a.ngroups * tiles;
+    const int bid = blockIdx.x % per_slice;
+    slice = __builtin_amdgcn_readfirstlane(blockIdx.x / per_slice);   // 0 unless the rows are split (host: grid = slices * per_slice)
+    group = bid / tiles;
+    tile = bid % tiles;
   }
   if (group >= a.ngroups) return;   // whole block; before any barrier
+  const bool split = a.rsplit > 1;
   // (the division runs in vector registers; the tile origin feeds scalar operands of the loads below)
   const int m0 = __builtin_amdgcn_readfirstlane((tile / nt_n) * BM), n0 = __builtin_amdgcn_readfirstlane((tile % nt_n) * BN);
   int r0 = 0, r1 = a.R;
   if (a.grp_offset) {
     r0 = a.grp_offset[group];
     r1 = a.grp_offset[group + 1];
+  } else if (split) {
+    r0 = min(a.R, slice * a.rslice);
+    r1 = min(a.R, r0 + a.rslice);
   }
   r0 = __builtin_amdgcn_readfirstlane(r0);
   r1 = __builtin_amdgcn_readfirstlane(r1);
@@ -307,9 +320,13 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
   const int frow = lane & 31, fk = lane >> 5;
   const int rows_left = min(a.M - (m0 + wm * 128), 128);
   const int cols_left = min(a.N - (n0 + wn * 128), 128);
-  const unsigned n_rec = rows_left > 0 && cols_left > 0 ? (unsigned)((rows_left - 1) * a.ldc + cols_left) * 4u : 0u;
+  // a row slice writes its partial product densely into the scratch tensor [slice][group][M][N] instead
+  const int ldc = split ? a.N : a.ldc;
+  const bool accumulate = !split && a.accumulate;
+  float* c_mat = split ? a.ws + ((long long)slice * a.ngroups + group) * ((long long)a.M * a.N) : a.C + widx * a.c_mat_stride;
+  const unsigned n_rec = rows_left > 0 && cols_left > 0 ? (unsigned)((rows_left - 1) * ldc + cols_left) * 4u : 0u;
   const unsigned long long c_tile = reinterpret_cast<unsigned long long>(
-      a.C + widx * a.c_mat_stride + (long long)(m0 + wm * 128) * a.ldc + n0 + wn * 128);
+      c_mat + (long long)(m0 + wm * 128) * ldc + n0 + wn * 128);
   const unsigned long long c_tile_u =   // the descriptor has to sit in scalar registers
       ((unsigned long long)__builtin_amdgcn_readfirstlane((unsigned)(c_tile >> 32)) << 32) |
       (unsigned)__builtin_amdgcn_readfirstlane((unsigned)c_tile);
@@ -324,9 +341,9 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int ml = mi * 32 + (e >> 2) * 8 + fk * 4 + (e & 3);
-        off[e] = nl < cols_left ? (unsigned)(ml * a.ldc + nl) * 4u : n_rec;
+        off[e] = nl < cols_left ? (unsigned)(ml * ldc + nl) * 4u : n_rec;
       }
-      if (a.accumulate) {   // block-uniform; the 16 loads of a tile are in flight together
+      if (accumulate) {   // block-uniform; the 16 loads of a tile are in flight together
         float old[16];
 #pragma unroll
         for (int e = 0; e < 16; ++e)
@@ -342,6 +359,32 @@ __global__ __launch_bounds__(256) void wgrad_bf16(const WgradArgs a) {
     }
 }
 }  // namespace wgd
+
+// Adds the row slices' partial products in slice order and writes (or adds) the sum: C[group] (=|+=) ws[0][group]
+// + ws[1][group] + ...  One thread per 4 output columns (host: N % 4 == 0, ldc % 4 == 0, 16-byte aligned bases).
+__global__ __launch_bounds__(256) void wgrad_reduce(const WgradArgs a) {
+  const long long quads_per_mat = (long long)a.M * (a.N / 4);
+  const long long total = quads_per_mat * a.ngroups;
+  const long long slice_stride = (long long)a.ngroups * a.M * a.N;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long long)gridDim.x * blockDim.x) {
+    const int group = (int)(i / quads_per_mat);
+    const long long q = i - group * quads_per_mat;
+    const int m = (int)(q / (a.N / 4)), n = (int)(q - (long long)m * (a.N / 4)) * 4;
+    const float* src = a.ws + (long long)group * a.M * a.N + (long long)m * a.N + n;
+    f32x4 sum = *reinterpret_cast<const f32x4*>(src);
+    for (int sl = 1; sl < a.rsplit; ++sl) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(src + sl * slice_stride);
+      sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    const long long widx = a.grp_widx ? a.grp_widx[group] : (a.w_base + group);
+    f32x4* dst = reinterpret_cast<f32x4*>(a.C + widx * a.c_mat_stride + (long long)m * a.ldc + n);
+    if (a.accumulate) {
+      const f32x4 old = *dst;
+      sum.x += old.x; sum.y += old.y; sum.z += old.z; sum.w += old.w;
+    }
+    *dst = sum;
+  }
+}
 
 // f32 path for parity-sized layers: one thread per output element, rows summed in order
 __global__ __launch_bounds__(256) void wgrad_f32(const WgradArgs a) {
@@ -365,14 +408,51 @@ __global__ __launch_bounds__(256) void wgrad_f32(const WgradArgs a) {
   *p = a.accumulate ? *p + sum : sum;
 }
 
+// Row slices for a product with fewer than 8 uniform groups of many rows (shared experts of a large batch): its
+// groups x tiles workgroups alone leave most of the chip idle.  Returns the number of slices (1 = no split) that
+// minimises rounds of workgroups x rows per slice, at most 8, each of at least 2048 rows; *rslice = rows per slice.
+static int choose_row_split(const occult_cfg_t& c, int ngroups, int M, int N, int R, int* rslice) {
+  *rslice = R;
+  if (c.dtype != OCCULT_BF16 || ngroups <= 0 || ngroups >= 8 || N % 4 != 0) return 1;
+  static int cached_cus = 0;   // compute units of the device first asked about (one kind of GPU per process)
+  if (cached_cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cached_cus = n;
+    else
+      cached_cus = 256;
+  }
+  const int cus = cached_cus;
+  const long long tiles = (long long)((M + wgd::BM - 1) / wgd::BM) * ((N + wgd::BN - 1) / wgd::BN) * ngroups;
+  int best = 1;
+  double best_cost = (double)((tiles + cus - 1) / cus) * R;
+  for (int r = 2; r <= 8; ++r) {
+    const int rows = ((R + r - 1) / r + wgd::BK - 1) / wgd::BK * wgd::BK;
+    if (rows < 2048) break;
+    const double cost = (double)((tiles * r + cus - 1) / cus) * rows;
+    if (cost < best_cost * 0.95) {
+      best = r;
+      best_cost = cost;
+      *rslice = rows;
+    }
+  }
+  return best;
+}
+
 static int launch_wgrad(const occult_cfg_t& c, const WgradArgs& a, hipStream_t s) {
   if (a.ngroups == 0 || a.M == 0 || a.N == 0) return OCCULT_OK;
   if (c.dtype == OCCULT_BF16) {
     const long long tiles = (long long)((a.M + wgd::BM - 1) / wgd::BM) * ((a.N + wgd::BN - 1) / wgd::BN);
-    const long long blocks = a.ngroups >= 8 ? (long long)((a.ngroups + 7) / 8) * tiles * 8 : (long long)a.ngroups * tiles;
+    long long blocks = a.ngroups >= 8 ? (long long)((a.ngroups + 7) / 8) * tiles * 8 : (long long)a.ngroups * tiles;
+    if (a.rsplit > 1) blocks *= a.rsplit;
     OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "weight-gradient grid too large");
     if (a.b_rows) hipLaunchKernelGGL(wgd::wgrad_bf16<true>, dim3((unsigned)blocks), dim3(256), 0, s, a);
     else hipLaunchKernelGGL(wgd::wgrad_bf16<false>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+    if (a.rsplit > 1) {
+      OCC_LAUNCH_CHECK("wgrad");
+      hipLaunchKernelGGL(wgrad_reduce, dim3(2048), dim3(256), 0, s, a);
+    }
   } else {
     OCC_REQUIRE(a.ngroups <= 65535, OCCULT_EINVAL, "too many groups");
     hipLaunchKernelGGL(wgrad_f32, dim3((a.N + 15) / 16, (a.M + 15) / 16, a.ngroups), dim3(256), 0, s, a);
@@ -385,14 +465,46 @@ static int launch_wgrad(const occult_cfg_t& c, const WgradArgs& a, hipStream_t s
 
 using namespace occult;
 
-extern "C" int occult_expert_ffn_backward_weights(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
-                                                  const void* x, const void* epd_h, const void* h_shared,
-                                                  const void* epd_dy, const void* dy, const void* epd_gu,
-                                                  const void* gu_shared, float* dw_gate, float* dw_up, float* dw_down,
-                                                  int accumulate, occult_stream_t stream) {
+// chooses the row split of a uniform-group product when the caller's scratch holds its partial sums
+static void set_row_split(const occult_cfg_t& c, WgradArgs& a, void* ws, size_t ws_bytes) {
+  a.rsplit = 0;
+  if (!ws) return;
+  int rslice = 0;
+  const int r = choose_row_split(c, a.ngroups, a.M, a.N, a.R, &rslice);
+  if (r > 1 && ws_bytes >= (size_t)r * a.ngroups * a.M * a.N * sizeof(float)) {
+    a.rsplit = r;
+    a.rslice = rslice;
+    a.ws = static_cast<float*>(ws);
+  }
+}
+
+// scratch for the row-split products of the shared experts: the largest of the three (they run one after another)
+static size_t wgrad_ws_need(const occult_cfg_t& c) {
+  if (c.S <= 0 || c.T <= 0) return 0;
+  int rs = 0;
+  const int r1 = choose_row_split(c, c.S, c.d, c.f, c.T, &rs);
+  const int r2 = choose_row_split(c, c.S, c.f, c.d, c.T, &rs);
+  const int r = r1 > r2 ? r1 : r2;
+  return r > 1 ? (size_t)r * c.S * c.d * c.f * sizeof(float) : 0;
+}
+
+extern "C" int occult_expert_ffn_backward_weights_ws_bytes(const occult_cfg_t* cfg, size_t* ws_bytes) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  OCC_REQUIRE(ws_bytes, OCCULT_ENULLPTR, "ws_bytes is NULL");
+  *ws_bytes = wgrad_ws_need(*cfg);
+  return OCCULT_OK;
+}
+
+static int backward_weights_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                 const void* x, const void* epd_h, const void* h_shared,
+                                 const void* epd_dy, const void* dy, const void* epd_gu,
+                                 const void* gu_shared, float* dw_gate, float* dw_up, float* dw_down,
+                                 int accumulate, void* ws, size_t ws_bytes, occult_stream_t stream) {
   int rc = check_cfg(cfg);
   if (rc) return rc;
   const occult_cfg_t c = *cfg;
+  OCC_REQUIRE(aligned16(ws), OCCULT_EALIGN, "ws is not 16-byte aligned");
   OCC_REQUIRE(dw_gate && dw_up && dw_down, OCCULT_ENULLPTR, "dw_gate, dw_up or dw_down is NULL");
   OCC_REQUIRE(accumulate == 0 || accumulate == 1, OCCULT_EINVAL, "accumulate=%d must be 0 or 1", accumulate);
   const int es = elem_size(c);
@@ -426,6 +538,7 @@ extern "C" int occult_expert_ffn_backward_weights(const occult_cfg_t* cfg, const
       a.A = sh ? dy : epd_dy; a.lda = c.d; a.M = c.d;
       a.B = sh ? h_shared : epd_h; a.ldb = sh ? c.S * c.f : c.f; a.b_group_cols = sh ? c.f : 0; a.N = c.f;
       a.C = dw_down; a.c_mat_stride = mat; a.ldc = c.f;
+      if (sh) set_row_split(c, a, ws, ws_bytes);
       rc = launch_wgrad(c, a, s);
       if (rc) return rc;
     }
@@ -435,9 +548,28 @@ extern "C" int occult_expert_ffn_backward_weights(const occult_cfg_t* cfg, const
       a.a_group_cols = sh ? 2 * c.f : 0; a.M = c.f;
       a.B = sh ? x : sfd_x; a.ldb = c.d; a.b_rows = sh ? nullptr : plan->epd_sfd_row; a.N = c.d;
       a.C = up ? dw_up : dw_gate; a.c_mat_stride = mat; a.ldc = c.d;
+      if (sh) set_row_split(c, a, ws, ws_bytes);
       rc = launch_wgrad(c, a, s);
       if (rc) return rc;
     }
   }
   return OCCULT_OK;
+}
+
+extern "C" int occult_expert_ffn_backward_weights(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                                  const void* x, const void* epd_h, const void* h_shared,
+                                                  const void* epd_dy, const void* dy, const void* epd_gu,
+                                                  const void* gu_shared, float* dw_gate, float* dw_up, float* dw_down,
+                                                  int accumulate, occult_stream_t stream) {
+  return backward_weights_impl(cfg, plan, sfd_x, x, epd_h, h_shared, epd_dy, dy, epd_gu, gu_shared, dw_gate, dw_up, dw_down,
+                               accumulate, nullptr, 0, stream);
+}
+
+extern "C" int occult_expert_ffn_backward_weights_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
+                                                     const void* x, const void* epd_h, const void* h_shared,
+                                                     const void* epd_dy, const void* dy, const void* epd_gu,
+                                                     const void* gu_shared, float* dw_gate, float* dw_up, float* dw_down,
+                                                     int accumulate, void* ws, size_t ws_bytes, occult_stream_t stream) {
+  return backward_weights_impl(cfg, plan, sfd_x, x, epd_h, h_shared, epd_dy, dy, epd_gu, gu_shared, dw_gate, dw_up, dw_down,
+                               accumulate, ws, ws_bytes, stream);
 }

@@ -213,7 +213,7 @@ class OccultLayer:
         self.gu_saved = False      # overwritten with [dg | du]
         return epd_dx, dx_sh
 
-    def expert_ffn_backward_weights(self, x, dy, accumulate=False):
+    def expert_ffn_backward_weights(self, x, dy, accumulate=False, use_ws=True):
         """f32 weight gradients dw_gate, dw_up [E+S, f, d], dw_down [E+S, d, f]; after expert_ffn_backward()."""
         s = self.shape
         n = s["E"] + s["S"]
@@ -222,9 +222,14 @@ class OccultLayer:
         dw_down = self._buf("dw_down", (n, s["d"], s["f"]), torch.float32)
         self._hidden(x, "x")
         self._hidden(dy, "dy")
-        B.occult_expert_ffn_backward_weights(self.cfg, self.plan, self.sfd_x, x, self.epd_h, self.h_shared, self.epd_dy,
-                                             dy, self.epd_gu, getattr(self, "gu_shared", None), dw_gate, dw_up, dw_down,
-                                             accumulate)
+        ws = None
+        if use_ws:   # scratch for the row slices of the shared experts' products (large T, few shared experts)
+            n = B.occult_expert_ffn_backward_weights_ws_bytes(self.cfg)
+            if n:
+                ws = self._buf("wgrad_ws", (n // 4,), torch.float32)
+        B.occult_expert_ffn_backward_weights_ws(self.cfg, self.plan, self.sfd_x, x, self.epd_h, self.h_shared, self.epd_dy,
+                                                dy, self.epd_gu, getattr(self, "gu_shared", None), dw_gate, dw_up, dw_down,
+                                                ws, accumulate)
         return dw_gate, dw_up, dw_down
 
     def backward_input(self, x, w_gate, w_up, dy):

@@ -170,6 +170,9 @@ SMALL = [
     # many experts with 160 rows or more and short hidden rows: the gathered weight-gradient product reads the
     # row indices of its fifth step while the loads issued before them are still in flight
     ("bf16_gather_steps", 2300, 576, 704, 64, 0, 4, 16, "bf16"),
+    # two shared experts over 5000 rows with one output tile each: their weight-gradient products are cut into row
+    # slices summed from scratch memory (the last slice ragged)
+    ("bf16_shared_row_slices", 5000, 128, 128, 4, 2, 1, 2, "bf16"),
 ]
 
 
@@ -207,6 +210,19 @@ def test_small_layers_backward_elementwise(name, T, d, f, E, S, k, D, dtype):
     for n, ref in (("dw_gate", "g_w_gate"), ("dw_up", "g_w_up"), ("dw_down", "g_w_down")):
         _check_per_matrix(n, grads[n], res[ref], dtype, get(rnd, ref))   # experts without rows: exact zeros
     _check_weight_grads_on_stored_operands(layer, shape, wk.x, dy, range(E))
+    if name == "bf16_shared_row_slices":
+        from paper_2505_13345_amd import binding as B
+        assert B.occult_expert_ffn_backward_weights_ws_bytes(layer.cfg) == 2 * S * d * f * 4 and layer.wgrad_ws is not None
+        # without the scratch the same products run unsplit: the same numbers up to the order of the f32 sums
+        unsplit = [g.clone() for g in layer.expert_ffn_backward_weights(to_dev(wk.x, dtype, require_gpu()),
+                                                                        to_dev(dy, dtype, require_gpu()), use_ws=False)]
+        torch.cuda.synchronize()
+        for n, u in zip(("dw_gate", "dw_up", "dw_down"), unsplit):
+            assert np.array_equal(u[:E].cpu().numpy(), grads[n][:E])                 # routed experts: untouched by the split
+            assert f32_rel_error(u[E:].cpu().numpy(), grads[n][E:]) <= 1e-5          # shared experts: other summation order
+            assert not np.array_equal(u[E:].cpu().numpy(), grads[n][E:])
+        layer.expert_ffn_backward_weights(to_dev(wk.x, dtype, require_gpu()), to_dev(dy, dtype, require_gpu()))
+        torch.cuda.synchronize()
     # accumulate = 1 adds the same product again: exactly twice the first result
     layer.expert_ffn_backward_weights(to_dev(wk.x, dtype, require_gpu()), to_dev(dy, dtype, require_gpu()), accumulate=True)
     torch.cuda.synchronize()
