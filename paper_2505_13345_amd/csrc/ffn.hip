@@ -283,29 +283,65 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 // are the row operand: a lane ends up with 4 consecutive output columns of one token (8-byte
 // stores).  The operands of the next K step (4 or 8 KiB of weights per wave) are in flight while
 // the current ones are multiplied; token blocks past the group's rows are skipped.
+//
+// One launch can carry two problems of the same shape class (N, K, SWIGLU, weight order): workgroups
+// [0, a_blocks) work on `first`, the rest on `second`.  A small batch's shared experts ride with its
+// routed experts this way: alone their few workgroups would stream weights at a fraction of the memory
+// system's rate, and run after the routed experts they would add their whole duration to the call.
 namespace skinny {
 constexpr int BN_OUT = 32;
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-template <bool SWIGLU, int MT, bool PACKED>   // MT token blocks of 16 per m-tile; PACKED: weights from a.Bp
-__global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
+// KSPLIT: the four waves of a workgroup take the four quarters of K of ONE column block and add their sums through
+// LDS (quarters in ascending order, so the result is reproducible) instead of taking four column blocks over the
+// whole K.  A wave's stream is then a quarter as long and there are four times as many workgroups, which the
+// hardware hands to whichever CU has room: with whole-K waves a layer's 2000-4000 waves fill the chip's 1024 SIMDs
+// two to four deep, all finish together, and a last partly filled layer of waves costs a whole stream's time.
+template <bool SWIGLU, int MT, bool PACKED, bool KSPLIT>   // MT token blocks of 16 per m-tile; PACKED: weights from a.Bp
+__global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, const GemmArgs second, const int a_blocks) {
   constexpr int BM = 16 * MT;
   constexpr int KS = MT <= 2 ? 2 : 1;   // 32-wide K steps per pipeline stage
   constexpr int NW = SWIGLU ? 2 : 1;
+  constexpr int CBW = KSPLIT ? 1 : 4;   // column blocks per workgroup
   static_assert(!PACKED || KS == 2, "the packed order is written for two K steps per stage");
   __shared__ TileInfo s_info;
+  const bool is_second = (int)blockIdx.x >= a_blocks;   // uniform over the workgroup
+  const GemmArgs& a = is_second ? second : first;
   const int n_cb = a.N / BN_OUT;   // column blocks (host: N % 32 == 0)
-  const int wgs_per_mt = (n_cb + 3) / 4;
-  const int mt = blockIdx.x / wgs_per_mt;
-  const TileInfo ti = find_tile<BM>(a, mt, &s_info);
+  const int wgs_per_mt = (n_cb + CBW - 1) / CBW;
+  int mt, cbq;   // m-tile and group of CBW column blocks
+  if (!is_second) {
+    mt = (int)blockIdx.x / wgs_per_mt;
+    cbq = (int)blockIdx.x % wgs_per_mt;
+  } else {
+    // Uniform groups of P m-tiles each: the P workgroups that stream the same weights (one per m-tile) get ids
+    // 8 apart, so they run on the same XCD (workgroups go to the 8 XCDs round-robin) at about the same time and
+    // all but the first of them find the weights in that XCD's L2.  unit = (group, four column blocks).
+    // (Measured against the four waves of one workgroup taking the m-tiles of one column block, which shares
+    // the weights inside a CU: that was slower from 64 tokens on.)
+    const int b = (int)blockIdx.x - a_blocks;
+    const int P = (a.M + BM - 1) / BM;
+    const int unit = b / (8 * P) * 8 + (b & 7), m = (b >> 3) % P;
+    if (unit >= a.ngroups * wgs_per_mt) return;   // uniform: the grid is padded to whole sets of 8 units
+    mt = unit / wgs_per_mt * P + m;
+    cbq = unit % wgs_per_mt;
+  }
+  TileInfo ti = find_tile<BM>(a, mt, &s_info);
   if (ti.group < 0) return;
+  // what came through LDS is the same in every lane: kept in scalar registers, so that the addresses built from it
+  // are a scalar base plus a per-lane 32-bit offset
+  ti.group = __builtin_amdgcn_readfirstlane(ti.group);
+  ti.m0 = __builtin_amdgcn_readfirstlane(ti.m0);
+  ti.rows = __builtin_amdgcn_readfirstlane(ti.rows);
+  ti.row_base = __builtin_amdgcn_readfirstlane(ti.row_base);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int cb = (blockIdx.x % wgs_per_mt) * 4 + wave;
-  if (cb >= n_cb) return;   // no barrier follows
+  const int cb = KSPLIT ? cbq : cbq * 4 + wave;
+  if (cb >= n_cb) return;   // without KSPLIT no barrier follows; with it this is never taken
   const int n0 = cb * BN_OUT;
   const int r = lane & 15, c = lane >> 4;
-  const long long widx = a.grp_widx ? a.grp_widx[ti.group] : (a.w_base + ti.group);
+  const long long widx = __builtin_amdgcn_readfirstlane(a.grp_widx ? a.grp_widx[ti.group] : (a.w_base + ti.group));
   const int nblk = min(MT, (ti.rows - ti.m0 + 15) / 16);   // token blocks with any valid row
+  const bool reread = is_second && a.M > BM;   // uniform
 
   // this lane's weight rows (column blocks 0 and 1 of the unit) and token rows, at its 16-byte K group
   const char* w[NW][2];
@@ -317,16 +353,19 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
                  ((widx * a.b_group_stride + (long long)(n0 + nb * 16 + r) * a.ldb) * 2 + c * 16);
   // packed order: this wave's unit is one contiguous stream of stages, a load instruction reads 1 KiB of it
   const char* wp = PACKED ? static_cast<const char*>(a.Bp) + widx * a.bp_group_stride +
-                                (long long)cb * (BN_OUT * NW * 2) * a.K + lane * 16
-                          : nullptr;
-  const char* xa[MT];
+                                (long long)cb * (BN_OUT * NW * 2) * a.K
+                          : nullptr;   // scalar; a lane reads at lane * 16 from it
+  const unsigned lane16 = lane * 16;
+  // token rows: a scalar base (this group's columns of A) plus a 32-bit byte offset per lane (host: A < 4 GiB)
+  const char* xbase = static_cast<const char*>(a.A) + (long long)ti.group * a.a_group_cols * 2;
+  unsigned xo[MT];
 #pragma unroll
   for (int tb = 0; tb < MT; ++tb) {
     int lr = ti.m0 + tb * 16 + r;
     if (lr >= ti.rows) lr = ti.rows - 1;   // tokens past the group's end repeat its last row; dropped at the end
     const int logical = ti.row_base + lr;
-    const long long src = a.a_rows ? a.a_rows[logical] : logical;
-    xa[tb] = static_cast<const char*>(a.A) + (src * a.lda * 2 + c * 16);
+    const unsigned src = a.a_rows ? a.a_rows[logical] : logical;
+    xo[tb] = (src * (unsigned)a.lda) * 2u + c * 16;
   }
 
   f32x4v acc[NW][2][MT];
@@ -361,14 +400,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
         for (int nb = 0; nb < 2; ++nb)
           {
             // measured: the streaming hint helps the single-matrix product and hurts the gate/up pair
-            const bf16x8* src = PACKED ? reinterpret_cast<const bf16x8*>(wp + (long long)i * (KS * NW * 2048) +
-                                                                           ((ks * NW + m) * 2 + nb) * 1024)
+            const bf16x8* src = PACKED ? reinterpret_cast<const bf16x8*>(wp + ((long long)i * (KS * NW * 2048) +
+                                                                                 ((ks * NW + m) * 2 + nb) * 1024) + (size_t)lane16)
                                        : reinterpret_cast<const bf16x8*>(w[m][nb] + woff + ks * 64);
-            st.wf[ks][m][nb] = SWIGLU ? *src : __builtin_nontemporal_load(src);
+            // (a problem whose groups span several m-tiles reads its weights once per m-tile: those stay cacheable)
+            st.wf[ks][m][nb] = (SWIGLU || reread) ? *src : __builtin_nontemporal_load(src);
           }
 #pragma unroll
       for (int tb = 0; tb < MT; ++tb)
-        if (tb < nblk) st.xf[ks][tb] = *reinterpret_cast<const bf16x8*>(xa[tb] + ((long long)i * KS + ks) * 64);
+        if (tb < nblk) st.xf[ks][tb] = *reinterpret_cast<const bf16x8*>(xbase + ((long long)i * KS + ks) * 64 + (size_t)xo[tb]);
     }
   };
   auto multiply = [&](const Stage& st) {
@@ -385,24 +425,67 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
         }
   };
 
-  Stage s0, s1;
-  load_stage(s0, w_off, 0);
-  for (int i = 0; i < nst; i += 2) {
-    // past the end the last stage is fetched again and not used
-    const bool more1 = i + 1 < nst;
-    if (more1) w_advance();
-    load_stage(s1, w_off, more1 ? i + 1 : i);
-    multiply(s0);
-    const bool more2 = i + 2 < nst;
-    if (more2) w_advance();
-    load_stage(s0, w_off, more2 ? i + 2 : (more1 ? i + 1 : i));
-    if (more1) multiply(s1);
+  // this wave's stages of K
+  const int i_begin = KSPLIT ? wave * nst / 4 : 0, i_end = KSPLIT ? (wave + 1) * nst / 4 : nst;
+  if (KSPLIT && i_begin > 0) {
+    const int kin = i_begin * 32 * KS, mat = kin / a.kseg;
+    w_kin = kin - mat * a.kseg;
+    w_off = ((long long)mat * a.b_group_stride + w_kin) * 2;
+  }
+  if (i_begin < i_end) {   // wave-uniform
+    Stage s0, s1;
+    load_stage(s0, w_off, i_begin);
+    for (int i = i_begin; i < i_end; i += 2) {
+      // past the end the last stage is fetched again and not used
+      const bool more1 = i + 1 < i_end;
+      if (more1) w_advance();
+      load_stage(s1, w_off, more1 ? i + 1 : i);
+      multiply(s0);
+      const bool more2 = i + 2 < i_end;
+      if (more2) w_advance();
+      load_stage(s0, w_off, more2 ? i + 2 : (more1 ? i + 1 : i));
+      if (more1) multiply(s1);
+    }
+  }
+  if constexpr (KSPLIT) {
+    // waves 1..3 hand their sums to wave 0, which adds them in that order and writes the tile
+    __shared__ float s_red[3][NW * 2 * MT * 4][64];
+    if (wave > 0) {
+#pragma unroll
+      for (int m = 0; m < NW; ++m)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int tb = 0; tb < MT; ++tb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s_red[wave - 1][((m * 2 + nb) * MT + tb) * 4 + e][lane] = acc[m][nb][tb][e];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int wv = 0; wv < 3; ++wv)
+#pragma unroll
+      for (int m = 0; m < NW; ++m)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int tb = 0; tb < MT; ++tb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[m][nb][tb][e] += s_red[wv][((m * 2 + nb) * MT + tb) * 4 + e][lane];
   }
 
   // acc element e of lane l: token l%16 of its block, output column nb*16 + (l/16)*4 + e of the unit
 #pragma unroll
   for (int tb = 0; tb < MT; ++tb) {
     const int token = ti.m0 + tb * 16 + r;
+    if (!SWIGLU && a.ws != nullptr) {   // uniform: this group's f32 product, summed over groups by the caller's reduction
+      if (token < ti.rows) {
+        float* wrow = a.ws + ((size_t)ti.group * a.M + token) * a.N + n0 + c * 4;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) *reinterpret_cast<f32x4v*>(wrow + nb * 16) = acc[0][nb][tb];
+      }
+      continue;
+    }
     if (token < ti.rows) {
       __bf16* crow = static_cast<__bf16*>(a.C) + (long long)(ti.row_base + token) * a.ldc + group_col0(a, ti.group) + n0 + c * 4;
 #pragma unroll
@@ -1066,6 +1149,39 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const u32x4* __restri
   }
 }
 
+// groups averaging under 24 rows take the weight-streaming kernel (one wave per 32 columns x 32 tokens)
+static bool streams_weights(const GemmArgs& a, int total_rows) {
+  // (that kernel addresses A rows with 32-bit byte offsets)
+  return (long long)total_rows < 24ll * a.ngroups && a.N % skinny::BN_OUT == 0 &&
+         (long long)a.a_rows_total * a.lda * 2 < (1ll << 32);
+}
+
+// The weight-streaming kernel over `a` (grouped rows, total_rows of them) and, when b is not NULL, over `b` in the
+// same launch (uniform groups of b->M rows; same N, K and weight order as `a`, one weight matrix along K in both).
+static int launch_skinny(const GemmArgs& a, const GemmArgs* b, bool swiglu, int total_rows, hipStream_t s) {
+  const bool ksplit = swiglu;   // the gate/up product's waves split K; the down projection's keep whole columns
+  const long long wgs_per_mt = ksplit ? a.N / skinny::BN_OUT : (a.N / skinny::BN_OUT + 3) / 4;
+  const long long a_blocks = ((total_rows + 31) / 32 + a.ngroups) * wgs_per_mt;
+  long long blocks = a_blocks;
+  if (b != nullptr) {
+    OCC_REQUIRE(b->N == a.N && b->K == a.K && b->grp_offset == nullptr && (b->Bp != nullptr) == (a.Bp != nullptr) &&
+                    b->kseg == b->K && a.kseg == a.K,
+                OCCULT_EINVAL, "the two problems of one weight-streaming launch differ in shape class");
+    blocks += (b->ngroups * wgs_per_mt + 7) / 8 * 8 * (long long)((b->M + 31) / 32);   // whole sets of 8 units
+  }
+  OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
+  const dim3 grid((unsigned)blocks), block(256);
+  const bool packed = a.Bp != nullptr && a.kseg == a.K;   // the packed order holds one matrix along K
+  const GemmArgs& b2 = b ? *b : a;
+  const int ab = (int)a_blocks;
+  if (swiglu && packed) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2, true, true>), grid, block, 0, s, a, b2, ab);
+  else if (swiglu) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2, false, true>), grid, block, 0, s, a, b2, ab);
+  else if (packed) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2, true, false>), grid, block, 0, s, a, b2, ab);
+  else hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2, false, false>), grid, block, 0, s, a, b2, ab);
+  OCC_LAUNCH_CHECK("grouped_gemm");
+  return OCCULT_OK;
+}
+
 // *fused_save: the pre-activations asked for through a.C2 were written by the launch itself
 static int launch_gemm_main(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s,
                             bool* fused_save_out) {
@@ -1084,21 +1200,8 @@ static int launch_gemm_main(const occult_cfg_t& c, const GemmArgs& a, bool swigl
     // only the 256-row tiles store the pre-activations themselves (not built with 64-bit offsets: registers)
     const bool fused_save = swiglu && a.C2 != nullptr && use_big && !wide;
     *fused_save_out = fused_save;
-    // groups averaging under 24 rows: weight streaming, one wave per 32 columns x 32 tokens
-    const bool use_skinny = !use_big && (long long)total_rows < 24ll * groups && a.N % skinny::BN_OUT == 0;
-    if (use_skinny) {
-      const long long m_tiles = (total_rows + 31) / 32 + a.ngroups;
-      const long long blocks = m_tiles * ((a.N / skinny::BN_OUT + 3) / 4);
-      OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
-      const dim3 grid((unsigned)blocks), block(256);
-      const bool packed = a.Bp != nullptr && a.kseg == a.K;   // the packed order holds one matrix along K
-      if (swiglu && packed) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2, true>), grid, block, 0, s, a);
-      else if (swiglu) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2, false>), grid, block, 0, s, a);
-      else if (packed) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2, true>), grid, block, 0, s, a);
-      else hipLaunchKernelGGL((skinny::grouped_gemm_bf16<false, 2, false>), grid, block, 0, s, a);
-      OCC_LAUNCH_CHECK("grouped_gemm");
-      return OCCULT_OK;
-    }
+    const bool use_skinny = !use_big && streams_weights(a, total_rows);
+    if (use_skinny) return launch_skinny(a, nullptr, swiglu, total_rows, s);
     const int bm = use_big ? t256::BM : small::BM;
     const int bn = use_big ? t256::BN : small::BN;
     const int bn_out = swiglu ? bn / 2 : bn;
@@ -1176,6 +1279,17 @@ using namespace occult;
 
 // Scratch that lets the shared experts' down projection of a small batch be split over K: the
 // product has T/128 x d/128 tiles only (16 for T = 128, d = 2048) with a long K = S*f.
+// Small batches whose routed experts take the weight-streaming kernel: the shared experts ride in the same two
+// launches, the down projection as one f32 product per shared expert in scratch, summed in expert order afterwards.
+constexpr int kPairMaxT = 128;   // a shared expert's weights are requested once per 32 tokens (from L2 after the first)
+static bool pairs_shared_with_routed(const occult_cfg_t& c) {
+  return c.dtype == OCCULT_BF16 && c.S > 0 && c.T > 0 && c.T <= kPairMaxT && (long long)c.T * c.k < 24ll * c.E &&
+         c.f % skinny::BN_OUT == 0 && c.d % skinny::BN_OUT == 0;
+}
+static size_t pair_ws_need(const occult_cfg_t& c) {
+  return pairs_shared_with_routed(c) ? (size_t)c.S * c.T * c.d * sizeof(float) : 0;
+}
+
 static size_t ffn_ws_need(const occult_cfg_t& c, int* ksplit_out) {
   *ksplit_out = 0;
   if (c.S == 0 || c.dtype != OCCULT_BF16 || c.T == 0) return 0;
@@ -1192,7 +1306,8 @@ extern "C" int occult_expert_ffn_ws_bytes(const occult_cfg_t* cfg, size_t* ws_by
   if (rc) return rc;
   OCC_REQUIRE(ws_bytes, OCCULT_ENULLPTR, "ws_bytes is NULL");
   int ks = 0;
-  *ws_bytes = ffn_ws_need(*cfg, &ks);
+  const size_t split = ffn_ws_need(*cfg, &ks), pair = pair_ws_need(*cfg);
+  *ws_bytes = split > pair ? split : pair;
   return OCCULT_OK;
 }
 
@@ -1291,6 +1406,49 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
     return OCCULT_OK;
   };
 
+  if (epd_gu == nullptr && gu_shared == nullptr && pairs_shared_with_routed(c) && ws != nullptr &&
+      ws_bytes >= pair_ws_need(c)) {
+    if (do1) {
+      GemmArgs g1{}, a1{};
+      g1.A = sfd_x; g1.lda = c.d; g1.a_rows = plan->epd_sfd_row;
+      a1.A = x; a1.lda = c.d;
+      g1.B = a1.B = weights->w_gate; g1.B2 = a1.B2 = weights->w_up;
+      g1.b_group_stride = a1.b_group_stride = (long long)c.f * c.d;
+      g1.ldb = a1.ldb = g1.kseg = a1.kseg = g1.K = a1.K = c.d;
+      g1.Bp = a1.Bp = packed; g1.bp_group_stride = a1.bp_group_stride = 4ll * c.f * c.d;
+      g1.N = a1.N = c.f;
+      g1.C = epd_h; g1.ldc = c.f;
+      a1.C = h_shared; a1.ldc = c.S * c.f; a1.c_group_cols = c.f;
+      g1.grp_offset = plan->exp_offset; g1.grp_widx = plan->pos_expert; g1.ngroups = c.E;
+      g1.a_rows_total = sfd_rows_max(c);
+      a1.w_base = c.E; a1.ngroups = c.S; a1.M = c.T; a1.a_rows_total = c.T;
+      rc = launch_skinny(g1, &a1, true, n_epd, s);
+      if (rc) return rc;
+    }
+    if (do2) {
+      GemmArgs g2{}, a2{};
+      g2.A = epd_h; g2.lda = c.f;
+      a2.A = h_shared; a2.lda = c.S * c.f; a2.a_group_cols = c.f;
+      g2.B = a2.B = weights->w_down;
+      g2.b_group_stride = a2.b_group_stride = (long long)c.d * c.f;
+      g2.ldb = a2.ldb = g2.kseg = a2.kseg = g2.K = a2.K = c.f;
+      if (packed) g2.Bp = a2.Bp = static_cast<const char*>(packed) + 4ll * c.f * c.d * (c.E + c.S);
+      g2.bp_group_stride = a2.bp_group_stride = 2ll * c.d * c.f;
+      g2.N = a2.N = c.d;
+      g2.C = epd_y; g2.ldc = c.d;
+      a2.C = y_shared; a2.ldc = c.d; a2.ws = static_cast<float*>(ws);
+      g2.grp_offset = plan->exp_offset; g2.grp_widx = plan->pos_expert; g2.ngroups = c.E;
+      g2.a_rows_total = n_epd;
+      a2.w_base = c.E; a2.ngroups = c.S; a2.M = c.T; a2.a_rows_total = c.T;
+      rc = launch_skinny(g2, &a2, false, n_epd, s);
+      if (rc) return rc;
+      const size_t quads = (size_t)c.T * c.d / 4;
+      hipLaunchKernelGGL(splitk_reduce_bf16, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
+                         static_cast<const float*>(ws), c.S, c.T, c.d, static_cast<__bf16*>(y_shared), c.d, 0);
+      OCC_LAUNCH_CHECK("splitk_reduce_bf16");
+    }
+    return OCCULT_OK;
+  }
   rc = routed_experts();
   if (rc) return rc;
   if (c.S > 0) {

@@ -248,10 +248,22 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
   }
 }
 
-// A batch of at most one block of tokens (T <= 256: decode steps): count, scan and fill in one launch
-// of one block.  The same ballots, popcounts and scan orders as the three kernels above, with the counts of
-// all devices and positions held in LDS instead of the block-count buffer, so every table comes out
-// bit-identical; what goes is two of three launches.
+// A batch of at most one block of tokens (T <= 256: decode steps): the whole plan in one launch of one block, and
+// without the per-column ballot loops of the three kernels above (D + E wave votes each for counting and for filling,
+// most of a small batch's planning time).  Each column (device or placement position) gets a 256-bit set of the tokens
+// that touch it, built with LDS bit-or (order-free, so deterministic); a token's rank in a column is then the number
+// of set bits below its own, the column's count the number of set bits, and every token writes its own table entries
+// from those.  The ranks are the same token-ascending ranks the sequential counters give: tables bit-identical to
+// the three-kernel path.
+__device__ __forceinline__ int bits_below(const unsigned long long* col, int t) {
+  const int tw = t >> 6;
+  const unsigned long long part = (1ull << (t & 63)) - 1ull;
+  int n = 0;
+#pragma unroll
+  for (int wd = 0; wd < 4; ++wd) n += __popcll(col[wd] & (wd < tw ? ~0ull : (wd == tw ? part : 0ull)));
+  return n;
+}
+
 template <int KMAX>
 __global__ __launch_bounds__(kTPB) void plan_single(
     const int32_t* __restrict__ ids, const float* __restrict__ w, int T, int k, int E, int D, int G, int M1,
@@ -260,111 +272,120 @@ __global__ __launch_bounds__(kTPB) void plan_single(
     int32_t* __restrict__ pos_expert, uint64_t* __restrict__ counters, int32_t* __restrict__ tok_sfd_row,
     int32_t* __restrict__ sfd_token, int32_t* __restrict__ epd_sfd_row, float* __restrict__ epd_gate,
     int32_t* __restrict__ sfd_epd_rows) {
+  static_assert(kTPB == 256, "token sets are four 64-bit words");
   __shared__ int s_pos[OCCULT_MAX_E];
-  __shared__ int s_cnt[kWavesPerBlock][kMaxCols];   // per-wave counts, then each wave's first rank
-  __shared__ int s_start[kMaxCols];                 // exclusive scans: devices, then positions
-  for (int e = threadIdx.x; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
-  __syncthreads();
-  const int t = threadIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __shared__ unsigned long long s_set[kMaxCols][4];   // columns: devices 0..D-1, then positions D..D+E-1
+  __shared__ int s_n[kMaxCols];                       // column counts
+  __shared__ int s_start[kMaxCols];                   // exclusive scans: devices, then positions
+  const int t = threadIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int C = D + E;
-  const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
+  for (int e = t; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
+  for (int i = t; i < C * 4; i += kTPB) (&s_set[0][0])[i] = 0ull;
+  __syncthreads();
+
+  // this token's positions and gates; a position named by several slots counts once, with the gate of the last
   int tpos[KMAX];
   float tgate[KMAX];
+  unsigned long long dev = 0;
 #pragma unroll
   for (int s = 0; s < KMAX; ++s) {
     const bool live = (t < T) && (s < k);
     tpos[s] = live ? s_pos[ids[(size_t)t * k + s]] : -1;
     tgate[s] = live ? w[(size_t)t * k + s] : 0.0f;
   }
-  if (t < T) tok_devmask[t] = b.dev;
-  for (int j = 0; j < D; ++j) {
-    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
-    if (lane == 0) s_cnt[wave][j] = __popcll(m);
-    for (int sl = 0; sl < G; ++sl) {
-      const unsigned long long mp = __ballot(has_pos(b, j * G + sl));
-      if (lane == 0) s_cnt[wave][D + j * G + sl] = __popcll(mp);
-    }
-  }
-  __syncthreads();
-  // column totals (into the scan array), then the two scans over devices and over positions
-  for (int c = threadIdx.x; c < C; c += kTPB) {
-    int tot = 0;
 #pragma unroll
-    for (int wv = 0; wv < kWavesPerBlock; ++wv) tot += s_cnt[wv][c];
-    s_start[c] = tot;
-  }
+  for (int s = 0; s < KMAX; ++s)
+#pragma unroll
+    for (int s2 = s + 1; s2 < KMAX; ++s2)
+      if (tpos[s] >= 0 && tpos[s2] == tpos[s]) tpos[s] = -1;
+  int tdev[KMAX];   // device of each surviving position
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) tdev[s] = tpos[s] >= 0 ? tpos[s] / G : -1;
+  const unsigned long long mybit = 1ull << (t & 63);
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s)
+    if (tpos[s] >= 0) {
+      const int j = tdev[s];
+      dev |= 1ull << j;
+      atomicOr(&s_set[D + tpos[s]][t >> 6], mybit);
+      atomicOr(&s_set[j][t >> 6], mybit);
+    }
+  if (t < T) tok_devmask[t] = dev;
   __syncthreads();
-  if (threadIdx.x == 0) {
+
+  for (int c = t; c < C; c += kTPB)
+    s_n[c] = __popcll(s_set[c][0]) + __popcll(s_set[c][1]) + __popcll(s_set[c][2]) + __popcll(s_set[c][3]);
+  __syncthreads();
+
+  // wave 0: devices; wave 1: positions (64 at a time, carrying the running total); waves 2, 3: inverse placement
+  if (wave < 2) {
+    const int n_cols = wave == 0 ? D : E, col0 = wave == 0 ? 0 : D;
+    int32_t* cnt_out = wave == 0 ? dev_count : exp_count;
+    int32_t* off_out = wave == 0 ? dev_offset : exp_offset;
     int run = 0, mx = 0;
-    for (int j = 0; j < D; ++j) {
-      const int n = s_start[j];
-      s_start[j] = run;
-      dev_count[j] = n;
-      dev_offset[j] = run;
-      mx = max(mx, n);
-      run += n;
-    }
-    dev_offset[D] = run;
-    counters[0] = (uint64_t)run;
-    counters[3] = (uint64_t)mx;
-  } else if (threadIdx.x == 64) {
-    int run = 0, mx = 0;
-    for (int P = 0; P < E; ++P) {
-      const int n = s_start[D + P];
-      s_start[D + P] = run;
-      exp_count[P] = n;
-      exp_offset[P] = run;
-      mx = max(mx, n);
-      run += n;
-    }
-    exp_offset[E] = run;
-    counters[1] = (uint64_t)run;
-    counters[2] = (uint64_t)T * (uint64_t)k;
-    counters[4] = (uint64_t)mx;
-    counters[5] = counters[6] = counters[7] = 0;
-  } else if (threadIdx.x >= 128) {
-    for (int e = threadIdx.x - 128; e < E; e += kTPB - 128) pos_expert[s_pos[e]] = e;
-  }
-  __syncthreads();
-  // per-wave counts -> first rank of each wave in each column
-  for (int c = threadIdx.x; c < C; c += kTPB) {
-    int run = s_start[c];
+    for (int c0 = 0; c0 < n_cols; c0 += 64) {
+      const int c = c0 + lane;
+      const int n = c < n_cols ? s_n[col0 + c] : 0;
+      int incl = n;
 #pragma unroll
-    for (int wv = 0; wv < kWavesPerBlock; ++wv) {
-      const int n = s_cnt[wv][c];
-      s_cnt[wv][c] = run;
-      run += n;
-    }
-  }
-  __syncthreads();
-  const int* first = s_cnt[wave];
-  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  for (int j = 0; j < D; ++j) {
-    const bool on = (b.dev >> j) & 1ull;
-    const unsigned long long m = __ballot(on);
-    const int r = on ? first[j] + __popcll(m & lt) : -1;
-    if (t < T) tok_sfd_row[(size_t)t * D + j] = r;
-    if (on) sfd_token[r] = t;
-    int filled = 0;   // merge-list entries of SFD row r written so far
-    for (int sl = 0; sl < G; ++sl) {
-      const int P = j * G + sl;
-      const bool hit = has_pos(b, P);
-      const unsigned long long me = __ballot(hit);
-      if (me == 0ull) continue;   // wave-uniform
-      if (hit) {
-        const int q = first[D + P] + __popcll(me & lt);
-        float gate = 0.0f;
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      if (c < n_cols) {
+        s_start[col0 + c] = run + incl - n;
+        cnt_out[c] = n;
+        off_out[c] = run + incl - n;
+      }
+      int m = n;
 #pragma unroll
-        for (int s = 0; s < KMAX; ++s) gate = (tpos[s] == P) ? tgate[s] : gate;
-        epd_sfd_row[q] = r;
-        epd_gate[q] = gate;
-        sfd_epd_rows[(size_t)r * M1 + filled] = q;
-        ++filled;
+      for (int o = 32; o > 0; o >>= 1) m = max(m, __shfl_xor(m, o, 64));
+      mx = max(mx, m);
+      run += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) {
+      off_out[n_cols] = run;
+      if (wave == 0) {
+        counters[0] = (uint64_t)run;
+        counters[3] = (uint64_t)mx;
+      } else {
+        counters[1] = (uint64_t)run;
+        counters[2] = (uint64_t)T * (uint64_t)k;
+        counters[4] = (uint64_t)mx;
+        counters[5] = counters[6] = counters[7] = 0;
       }
     }
-    if (on)
+  } else {
+    for (int e = t - 128; e < E; e += kTPB - 128) pos_expert[s_pos[e]] = e;
+  }
+  __syncthreads();
+
+  if (t >= T) return;
+  for (int j = 0; j < D; ++j) {
+    const bool on = (dev >> j) & 1ull;
+    const int r = on ? s_start[j] + bits_below(s_set[j], t) : -1;
+    tok_sfd_row[(size_t)t * D + j] = r;
+    if (on) {
+      sfd_token[r] = t;
+      int filled = 0;
+#pragma unroll
+      for (int s = 0; s < KMAX; ++s) filled += tdev[s] == j ? 1 : 0;
       for (int i = filled; i < M1; ++i) sfd_epd_rows[(size_t)r * M1 + i] = -1;
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    const int P = tpos[s];
+    if (P < 0) continue;
+    const int j = tdev[s];
+    const int r = s_start[j] + bits_below(s_set[j], t);
+    const int q = s_start[D + P] + bits_below(s_set[D + P], t);
+    int before = 0;   // this token's other positions on the same device below P: the merge list is position-ascending
+#pragma unroll
+    for (int s2 = 0; s2 < KMAX; ++s2) before += (tdev[s2] == j && tpos[s2] < P) ? 1 : 0;
+    epd_sfd_row[q] = r;
+    epd_gate[q] = tgate[s];
+    sfd_epd_rows[(size_t)r * M1 + before] = q;
   }
 }
 
