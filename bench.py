@@ -117,7 +117,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="replay one captured HIP graph per step instead of launching every call from the host "
-                         "(measured: no faster on this runtime, 0.376 vs 0.363 ms on the decode workload)")
+                         "(measured: no faster on this runtime, 0.264 vs 0.252 ms on the decode workload)")
     ap.add_argument("--no-standard", action="store_true",
                     help="skip the comparison run with one simulated device per expert (standard dispatch)")
     ap.add_argument("--placement", action="store_true",
@@ -130,6 +130,10 @@ def main():
     ap.add_argument("--merge-atomic", action="store_true",
                     help="also time occult_combine_atomic (the paper's atomic first-stage merge: f32 and packed bf16 atomics) "
                          "beside occult_combine")
+    ap.add_argument("--gemm-context", action="store_true",
+                    help="bf16 workloads: also time the two expert products on all-zero operands (the clock under matrix "
+                         "load is power-limited, so operand values change the rate) and the vendor library's dense "
+                         "bf16 GEMMs of the same row count and shapes (torch.matmul) on values of the workload's scale")
     ap.add_argument("--cpu-sample", type=int, default=16384)
     ap.add_argument("--call-reps", type=int, default=10)
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -440,6 +444,40 @@ def main():
                                "note": "clear + atomic merge + stage 2 (three kernels) against the fused order-fixed occult_combine"}
         layer.combine()
         layer.sfd_acc = None
+        torch.cuda.empty_cache()
+    if args.gemm_context and shape.dtype == "bf16":
+        n_rows = n_epd + S * T
+
+        def two_products(xx, a, b, c):
+            layer.dispatch(xx)
+            res = {}
+            for ph, name, fl in ((1, "gemm1_swiglu", flops1), (2, "gemm2_down", flops2)):
+                layer.cfg.ffn_phase = ph
+                ms = _event_time_ms(lambda: layer.expert_ffn(xx, a, b, c), r)
+                res[name] = {"ms": ms, "tflops": fl / ms / 1e9, "frac_of_peak": fl / ms / 1e9 / 2500.0}
+            layer.cfg.ffn_phase = 0
+            return res
+
+        ctx = {"expert_gemm_workload_values": two_products(x, wg, wu, wd)}
+        zx, zg, zd = torch.zeros_like(x), torch.zeros_like(wg), torch.zeros_like(wd)
+        ctx["expert_gemm_zero_operands"] = two_products(zx, zg, zg, zd)
+        del zx, zg, zd
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+        lib = {}
+        for name, kk, nn, fl in (("dense_gemm1_shape", d, 2 * f, flops1), ("dense_gemm2_shape", f, d, flops2)):
+            pa = torch.randn(n_rows, kk, device=dev, generator=gen).to(tdt)
+            pb = (torch.randn(nn, kk, device=dev, generator=gen) / kk ** 0.5).to(tdt)
+            ms = _event_time_ms(lambda: torch.matmul(pa, pb.t()), r)
+            lib[name] = {"m": n_rows, "n": nn, "k": kk, "ms": ms, "tflops": fl / ms / 1e9,
+                         "frac_of_peak": fl / ms / 1e9 / 2500.0}
+            del pa, pb
+        ctx["vendor_library_dense_bf16"] = lib
+        ctx["note"] = ("same row count and flops as the two expert products; the library GEMMs have no row gather, no "
+                       "groups, no ragged tiles and no fused activation")
+        out["gemm_context"] = ctx
+        layer.dispatch(x)
+        layer.expert_ffn(x, wg, wu, wd)
         torch.cuda.empty_cache()
     if backward is not None:
         out["backward"] = backward

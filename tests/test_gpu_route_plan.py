@@ -103,6 +103,18 @@ PLAN_CASES = [
     (256, 64, 32, 600, "random"),
     (256, 4, 3, 1300, "random"),
     (8, 2, 8, 300, "contig"),         # k = E: every token on every device
+    # one block of tokens (T <= 256): the single-launch planner built on per-column token sets
+    (8, 2, 2, 1, "contig"),
+    (60, 4, 4, 63, "random"),
+    (60, 4, 4, 64, "contig"),
+    (60, 4, 4, 65, "random"),
+    (64, 8, 8, 129, "random"),
+    (64, 64, 8, 200, "contig"),       # one expert per device
+    (64, 1, 8, 256, "contig"),        # one device
+    (256, 64, 32, 256, "random"),     # the largest layer the planner takes, full block
+    (256, 4, 3, 191, "random"),
+    (8, 2, 8, 100, "contig"),         # k = E
+    (32, 4, 16, 77, "random"),
 ]
 
 
