@@ -217,18 +217,16 @@ int occult_expert_ffn(const occult_cfg_t* cfg, const occult_plan_t* plan, const 
                       const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,
                       void* h_shared, void* y_shared, occult_stream_t stream);
 
-/* occult_expert_ffn with a scratch buffer, for small batches (T < 192) with shared experts, whose
- * products alone leave most of the chip idle.  Given `ws` (device ptr, 16-byte aligned,
- * >= occult_expert_ffn_ws_bytes() bytes):
- *  - bf16, T <= 128 and fewer than 24 rows per routed expert on average: the shared experts are
- *    computed inside the routed experts' two launches; their down projection is written as one f32
- *    product per shared expert into ws and added in expert order, rounded once;
- *  - otherwise (24 <= T < 192) the shared down projection (few output tiles, K = S*f) is split
- *    over K into f32 partial sums in ws that a second kernel adds in slice order and rounds once.
- * Either way y_shared differs from occult_expert_ffn's only by the order of f32 additions; epd_h
- * and epd_y are the same bits.  With ws == NULL, too few bytes, or a layer that does not need it
- * (ws_bytes == 0), identical to occult_expert_ffn.  The contents of ws are not kept between calls
- * and need no initialisation. */
+/* occult_expert_ffn with a scratch buffer, for small batches with shared experts whose down
+ * projection alone (few output tiles, K = S*f) leaves most of the chip idle: 24 <= T < 192, unless
+ * the batch is one whose shared experts are computed inside the routed experts' two launches
+ * anyway (bf16, T <= 128 and fewer than 24 rows per routed expert on average: no scratch, ws_bytes
+ * = 0).  Given `ws` (device ptr, 16-byte aligned, >= occult_expert_ffn_ws_bytes() bytes) that
+ * product is split over K into f32 partial sums in ws, which a second kernel adds in slice order and
+ * rounds once: y_shared then differs from occult_expert_ffn's only by the order of f32 additions;
+ * epd_h and epd_y are the same bits.  With ws == NULL, too few bytes, or a layer that does not need
+ * it (ws_bytes == 0), identical to occult_expert_ffn.  The contents of ws are not kept between
+ * calls and need no initialisation. */
 int occult_expert_ffn_ws_bytes(const occult_cfg_t* cfg, size_t* ws_bytes);
 int occult_expert_ffn_ws(const occult_cfg_t* cfg, const occult_plan_t* plan, const void* sfd_x,
                          const void* x, const occult_weights_t* weights, void* epd_h, void* epd_y,

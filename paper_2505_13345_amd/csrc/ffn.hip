@@ -284,15 +284,18 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 // stores).  The operands of the next K step (4 or 8 KiB of weights per wave) are in flight while
 // the current ones are multiplied; token blocks past the group's rows are skipped.
 //
-// One launch can carry two problems of the same shape class (N, K, SWIGLU, weight order): workgroups
+// One launch can carry two problems of the same shape class (N, SWIGLU, weight order): workgroups
 // [0, a_blocks) work on `first`, the rest on `second`.  A small batch's shared experts ride with its
 // routed experts this way: alone their few workgroups would stream weights at a fraction of the memory
 // system's rate, and run after the routed experts they would add their whole duration to the call.
+// The second problem has uniform groups and always splits K over the four waves of a workgroup (below);
+// its K may walk several weight matrices (the shared experts' down projection: K = S * f), so that
+// the sum over the shared experts happens in the accumulators and in the in-LDS addition, in K order.
 namespace skinny {
 constexpr int BN_OUT = 32;
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-// KSPLIT: the four waves of a workgroup take the four quarters of K of ONE column block and add their sums through
+// KSPLIT (first problem; the second always): the four waves of a workgroup take the four quarters of K of ONE column block and add their sums through
 // LDS (quarters in ascending order, so the result is reproducible) instead of taking four column blocks over the
 // whole K.  A wave's stream is then a quarter as long and there are four times as many workgroups, which the
 // hardware hands to whichever CU has room: with whole-K waves a layer's 2000-4000 waves fill the chip's 1024 SIMDs
@@ -302,14 +305,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
   constexpr int BM = 16 * MT;
   constexpr int KS = MT <= 2 ? 2 : 1;   // 32-wide K steps per pipeline stage
   constexpr int NW = SWIGLU ? 2 : 1;
-  constexpr int CBW = KSPLIT ? 1 : 4;   // column blocks per workgroup
   static_assert(!PACKED || KS == 2, "the packed order is written for two K steps per stage");
   __shared__ TileInfo s_info;
   const bool is_second = (int)blockIdx.x >= a_blocks;   // uniform over the workgroup
   const GemmArgs& a = is_second ? second : first;
+  const bool ksplit = KSPLIT || is_second;   // uniform: the second problem's workgroups always split K
+  const int cbw = ksplit ? 1 : 4;            // column blocks per workgroup
   const int n_cb = a.N / BN_OUT;   // column blocks (host: N % 32 == 0)
-  const int wgs_per_mt = (n_cb + CBW - 1) / CBW;
-  int mt, cbq;   // m-tile and group of CBW column blocks
+  const int wgs_per_mt = (n_cb + cbw - 1) / cbw;
+  int mt, cbq;   // m-tile and group of cbw column blocks
   if (!is_second) {
     mt = (int)blockIdx.x / wgs_per_mt;
     cbq = (int)blockIdx.x % wgs_per_mt;
@@ -335,8 +339,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
   ti.rows = __builtin_amdgcn_readfirstlane(ti.rows);
   ti.row_base = __builtin_amdgcn_readfirstlane(ti.row_base);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int cb = KSPLIT ? cbq : cbq * 4 + wave;
-  if (cb >= n_cb) return;   // without KSPLIT no barrier follows; with it this is never taken
+  const int cb = ksplit ? cbq : cbq * 4 + wave;
+  if (cb >= n_cb) return;   // whole-K workgroups meet no barrier after this; K-splitting ones never take it
   const int n0 = cb * BN_OUT;
   const int r = lane & 15, c = lane >> 4;
   const long long widx = __builtin_amdgcn_readfirstlane(a.grp_widx ? a.grp_widx[ti.group] : (a.w_base + ti.group));
@@ -352,12 +356,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
       w[m][nb] = static_cast<const char*>(m == 0 ? a.B : a.B2) +
                  ((widx * a.b_group_stride + (long long)(n0 + nb * 16 + r) * a.ldb) * 2 + c * 16);
   // packed order: this wave's unit is one contiguous stream of stages, a load instruction reads 1 KiB of it
-  const char* wp = PACKED ? static_cast<const char*>(a.Bp) + widx * a.bp_group_stride +
-                                (long long)cb * (BN_OUT * NW * 2) * a.K
+  const long long unit_bytes = (long long)(BN_OUT * NW * 2) * a.kseg;   // one unit's stream inside one weight matrix
+  const char* wp = PACKED ? static_cast<const char*>(a.Bp) + widx * a.bp_group_stride + cb * unit_bytes
                           : nullptr;   // scalar; a lane reads at lane * 16 from it
   const unsigned lane16 = lane * 16;
-  // token rows: a scalar base (this group's columns of A) plus a 32-bit byte offset per lane (host: A < 4 GiB)
-  const char* xbase = static_cast<const char*>(a.A) + (long long)ti.group * a.a_group_cols * 2;
+  // token rows: a scalar base plus a 32-bit byte offset per lane (host: A < 4 GiB)
+  const char* xbase = static_cast<const char*>(a.A);
   unsigned xo[MT];
 #pragma unroll
   for (int tb = 0; tb < MT; ++tb) {
@@ -378,20 +382,22 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
 
   const int nst = a.K / (32 * KS);   // pipeline stages along K (host: K % 64 == 0)
   // byte offset of the current stage inside a weight row; K > kseg walks consecutive weight matrices
-  long long w_off = 0;
+  long long w_off = 0, p_off = 0;   // caller's layout / packed order
   int w_kin = 0;
   auto w_advance = [&]() {
     w_off += 64 * KS;
+    p_off += KS * NW * 2048;
     w_kin += 32 * KS;
     if (w_kin >= a.kseg) {   // host: kseg % 64 == 0, so a stage never straddles two matrices
       w_kin = 0;
       w_off += (a.b_group_stride - a.kseg) * 2;
+      p_off += a.bp_group_stride - unit_bytes;
     }
   };
   struct Stage {
     bf16x8 wf[KS][NW][2], xf[KS][MT];
   };
-  auto load_stage = [&](Stage& st, long long woff, int i) {
+  auto load_stage = [&](Stage& st, long long woff, long long poff, int i) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
@@ -400,8 +406,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
         for (int nb = 0; nb < 2; ++nb)
           {
             // measured: the streaming hint helps the single-matrix product and hurts the gate/up pair
-            const bf16x8* src = PACKED ? reinterpret_cast<const bf16x8*>(wp + ((long long)i * (KS * NW * 2048) +
-                                                                                 ((ks * NW + m) * 2 + nb) * 1024) + (size_t)lane16)
+            const bf16x8* src = PACKED ? reinterpret_cast<const bf16x8*>(wp + (poff + ((ks * NW + m) * 2 + nb) * 1024) +
+                                                                           (size_t)lane16)
                                        : reinterpret_cast<const bf16x8*>(w[m][nb] + woff + ks * 64);
             // (a problem whose groups span several m-tiles reads its weights once per m-tile: those stay cacheable)
             st.wf[ks][m][nb] = (SWIGLU || reread) ? *src : __builtin_nontemporal_load(src);
@@ -426,28 +432,29 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
   };
 
   // this wave's stages of K
-  const int i_begin = KSPLIT ? wave * nst / 4 : 0, i_end = KSPLIT ? (wave + 1) * nst / 4 : nst;
-  if (KSPLIT && i_begin > 0) {
+  const int i_begin = ksplit ? wave * nst / 4 : 0, i_end = ksplit ? (wave + 1) * nst / 4 : nst;
+  if (i_begin > 0) {
     const int kin = i_begin * 32 * KS, mat = kin / a.kseg;
     w_kin = kin - mat * a.kseg;
     w_off = ((long long)mat * a.b_group_stride + w_kin) * 2;
+    p_off = mat * a.bp_group_stride + (long long)(w_kin / 32) * (NW * 2048);
   }
   if (i_begin < i_end) {   // wave-uniform
     Stage s0, s1;
-    load_stage(s0, w_off, i_begin);
+    load_stage(s0, w_off, p_off, i_begin);
     for (int i = i_begin; i < i_end; i += 2) {
       // past the end the last stage is fetched again and not used
       const bool more1 = i + 1 < i_end;
       if (more1) w_advance();
-      load_stage(s1, w_off, more1 ? i + 1 : i);
+      load_stage(s1, w_off, p_off, more1 ? i + 1 : i);
       multiply(s0);
       const bool more2 = i + 2 < i_end;
       if (more2) w_advance();
-      load_stage(s0, w_off, more2 ? i + 2 : (more1 ? i + 1 : i));
+      load_stage(s0, w_off, p_off, more2 ? i + 2 : (more1 ? i + 1 : i));
       if (more1) multiply(s1);
     }
   }
-  if constexpr (KSPLIT) {
+  if (ksplit) {   // uniform over the workgroup
     // waves 1..3 hand their sums to wave 0, which adds them in that order and writes the tile
     __shared__ float s_red[3][NW * 2 * MT * 4][64];
     if (wave > 0) {
@@ -478,14 +485,6 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
 #pragma unroll
   for (int tb = 0; tb < MT; ++tb) {
     const int token = ti.m0 + tb * 16 + r;
-    if (!SWIGLU && a.ws != nullptr) {   // uniform: this group's f32 product, summed over groups by the caller's reduction
-      if (token < ti.rows) {
-        float* wrow = a.ws + ((size_t)ti.group * a.M + token) * a.N + n0 + c * 4;
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb) *reinterpret_cast<f32x4v*>(wrow + nb * 16) = acc[0][nb][tb];
-      }
-      continue;
-    }
     if (token < ti.rows) {
       __bf16* crow = static_cast<__bf16*>(a.C) + (long long)(ti.row_base + token) * a.ldc + group_col0(a, ti.group) + n0 + c * 4;
 #pragma unroll
@@ -1160,18 +1159,20 @@ static bool streams_weights(const GemmArgs& a, int total_rows) {
 // same launch (uniform groups of b->M rows; same N, K and weight order as `a`, one weight matrix along K in both).
 static int launch_skinny(const GemmArgs& a, const GemmArgs* b, bool swiglu, int total_rows, hipStream_t s) {
   const bool ksplit = swiglu;   // the gate/up product's waves split K; the down projection's keep whole columns
-  const long long wgs_per_mt = ksplit ? a.N / skinny::BN_OUT : (a.N / skinny::BN_OUT + 3) / 4;
+  const long long n_cb = a.N / skinny::BN_OUT;
+  const long long wgs_per_mt = ksplit ? n_cb : (n_cb + 3) / 4;
   const long long a_blocks = ((total_rows + 31) / 32 + a.ngroups) * wgs_per_mt;
   long long blocks = a_blocks;
   if (b != nullptr) {
-    OCC_REQUIRE(b->N == a.N && b->K == a.K && b->grp_offset == nullptr && (b->Bp != nullptr) == (a.Bp != nullptr) &&
-                    b->kseg == b->K && a.kseg == a.K,
+    OCC_REQUIRE(b->N == a.N && b->grp_offset == nullptr && (b->Bp != nullptr) == (a.Bp != nullptr) && a.kseg == a.K &&
+                    b->K % b->kseg == 0,
                 OCCULT_EINVAL, "the two problems of one weight-streaming launch differ in shape class");
-    blocks += (b->ngroups * wgs_per_mt + 7) / 8 * 8 * (long long)((b->M + 31) / 32);   // whole sets of 8 units
+    blocks += (b->ngroups * n_cb + 7) / 8 * 8 * (long long)((b->M + 31) / 32);   // whole sets of 8 units
   }
   OCC_REQUIRE(blocks < (1ll << 31), OCCULT_EINVAL, "grouped GEMM grid too large");
   const dim3 grid((unsigned)blocks), block(256);
-  const bool packed = a.Bp != nullptr && a.kseg == a.K;   // the packed order holds one matrix along K
+  // the packed order holds whole matrices: a K that walks several of them steps from one matrix's stream to the next
+  const bool packed = a.Bp != nullptr && (a.kseg == a.K || a.K % a.kseg == 0);
   const GemmArgs& b2 = b ? *b : a;
   const int ab = (int)a_blocks;
   if (swiglu && packed) hipLaunchKernelGGL((skinny::grouped_gemm_bf16<true, 2, true, true>), grid, block, 0, s, a, b2, ab);
@@ -1254,21 +1255,25 @@ static int launch_gemm_main(const occult_cfg_t& c, const GemmArgs& a, bool swigl
   return OCCULT_OK;
 }
 
+// The two pre-activations of a gate/up product `a` (a.C2) as two more products without the activation: only the
+// 256-row tiles store them from the product's own launch.
+static int launch_preactivations(const occult_cfg_t& c, const GemmArgs& a, int total_rows, hipStream_t s) {
+  bool fused_save = false;
+  GemmArgs p = a;
+  p.C = a.C2; p.ldc = 2 * a.ldc; p.c_group_cols = 2 * a.c_group_cols; p.C2 = nullptr; p.B2 = nullptr; p.Bp = nullptr;
+  p.c_col0 = 2 * a.c_col0;
+  int rc = launch_gemm_main(c, p, false, total_rows, s, &fused_save);
+  if (rc) return rc;
+  p.B = a.B2; p.c_col0 = 2 * a.c_col0 + a.N;
+  return launch_gemm_main(c, p, false, total_rows, s, &fused_save);
+}
+
 int launch_gemm(const occult_cfg_t& c, const GemmArgs& a, bool swiglu, int total_rows, hipStream_t s) {
   if (total_rows == 0) return OCCULT_OK;
   bool fused_save = false;
   int rc = launch_gemm_main(c, a, swiglu, total_rows, s, &fused_save);
   if (rc) return rc;
-  if (swiglu && a.C2 != nullptr && !fused_save) {
-    // the other kernels do not store pre-activations: two more products without the activation
-    GemmArgs p = a;
-    p.C = a.C2; p.ldc = 2 * a.ldc; p.c_group_cols = 2 * a.c_group_cols; p.C2 = nullptr; p.B2 = nullptr; p.Bp = nullptr;
-    p.c_col0 = 2 * a.c_col0;
-    rc = launch_gemm_main(c, p, false, total_rows, s, &fused_save);
-    if (rc) return rc;
-    p.B = a.B2; p.c_col0 = 2 * a.c_col0 + a.N;
-    rc = launch_gemm_main(c, p, false, total_rows, s, &fused_save);
-  }
+  if (swiglu && a.C2 != nullptr && !fused_save) rc = launch_preactivations(c, a, total_rows, s);
   return rc;
 }
 
@@ -1280,20 +1285,20 @@ using namespace occult;
 // Scratch that lets the shared experts' down projection of a small batch be split over K: the
 // product has T/128 x d/128 tiles only (16 for T = 128, d = 2048) with a long K = S*f.
 // Small batches whose routed experts take the weight-streaming kernel: the shared experts ride in the same two
-// launches, the down projection as one f32 product per shared expert in scratch, summed in expert order afterwards.
+// launches, the down projection as one product whose K walks the S matrices (no scratch, no extra launch).
 constexpr int kPairMaxT = 128;   // a shared expert's weights are requested once per 32 tokens (from L2 after the first)
 static bool pairs_shared_with_routed(const occult_cfg_t& c) {
   return c.dtype == OCCULT_BF16 && c.S > 0 && c.T > 0 && c.T <= kPairMaxT && (long long)c.T * c.k < 24ll * c.E &&
-         c.f % skinny::BN_OUT == 0 && c.d % skinny::BN_OUT == 0;
-}
-static size_t pair_ws_need(const occult_cfg_t& c) {
-  return pairs_shared_with_routed(c) ? (size_t)c.S * c.T * c.d * sizeof(float) : 0;
+         c.f % skinny::BN_OUT == 0 && c.d % skinny::BN_OUT == 0 &&
+         (long long)sfd_rows_max(c) * c.d * 2 < (1ll << 32) && (long long)c.T * c.k * c.f * 2 < (1ll << 32) &&
+         (long long)c.T * c.S * c.f * 2 < (1ll << 32);
 }
 
 static size_t ffn_ws_need(const occult_cfg_t& c, int* ksplit_out) {
   *ksplit_out = 0;
   if (c.S == 0 || c.dtype != OCCULT_BF16 || c.T == 0) return 0;
   if (c.T < 24) return 0;   // those batches take the weight-streaming kernel
+  if (pairs_shared_with_routed(c)) return 0;   // the shared experts run inside the routed experts' launches
   const long long tiles = (long long)((c.T + 127) / 128) * ((c.d + 127) / 128);
   const int ks = choose_ksplit(tiles, c.S * c.f / 64);
   if (ks == 0 || c.d % 4 != 0) return 0;
@@ -1306,8 +1311,7 @@ extern "C" int occult_expert_ffn_ws_bytes(const occult_cfg_t* cfg, size_t* ws_by
   if (rc) return rc;
   OCC_REQUIRE(ws_bytes, OCCULT_ENULLPTR, "ws_bytes is NULL");
   int ks = 0;
-  const size_t split = ffn_ws_need(*cfg, &ks), pair = pair_ws_need(*cfg);
-  *ws_bytes = split > pair ? split : pair;
+  *ws_bytes = ffn_ws_need(*cfg, &ks);
   return OCCULT_OK;
 }
 
@@ -1406,8 +1410,7 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
     return OCCULT_OK;
   };
 
-  if (epd_gu == nullptr && gu_shared == nullptr && pairs_shared_with_routed(c) && ws != nullptr &&
-      ws_bytes >= pair_ws_need(c)) {
+  if (pairs_shared_with_routed(c)) {
     if (do1) {
       GemmArgs g1{}, a1{};
       g1.A = sfd_x; g1.lda = c.d; g1.a_rows = plan->epd_sfd_row;
@@ -1424,28 +1427,35 @@ static int expert_ffn_impl(const occult_cfg_t* cfg, const occult_plan_t* plan, c
       a1.w_base = c.E; a1.ngroups = c.S; a1.M = c.T; a1.a_rows_total = c.T;
       rc = launch_skinny(g1, &a1, true, n_epd, s);
       if (rc) return rc;
+      if (epd_gu != nullptr) {   // a training step keeps the pre-activations: rows of 2f, [gate | up]
+        g1.C2 = epd_gu;
+        rc = launch_preactivations(c, g1, n_epd, s);
+        if (rc) return rc;
+      }
+      if (gu_shared != nullptr) {   // rows of S * 2f: per shared expert [gate | up]
+        a1.C2 = gu_shared;
+        rc = launch_preactivations(c, a1, c.T * c.S, s);
+        if (rc) return rc;
+      }
     }
     if (do2) {
       GemmArgs g2{}, a2{};
       g2.A = epd_h; g2.lda = c.f;
-      a2.A = h_shared; a2.lda = c.S * c.f; a2.a_group_cols = c.f;
+      a2.A = h_shared; a2.lda = c.S * c.f;
       g2.B = a2.B = weights->w_down;
       g2.b_group_stride = a2.b_group_stride = (long long)c.d * c.f;
-      g2.ldb = a2.ldb = g2.kseg = a2.kseg = g2.K = a2.K = c.f;
+      g2.ldb = a2.ldb = g2.kseg = a2.kseg = g2.K = c.f;
+      a2.K = c.S * c.f;   // one product over the S down matrices
       if (packed) g2.Bp = a2.Bp = static_cast<const char*>(packed) + 4ll * c.f * c.d * (c.E + c.S);
       g2.bp_group_stride = a2.bp_group_stride = 2ll * c.d * c.f;
       g2.N = a2.N = c.d;
       g2.C = epd_y; g2.ldc = c.d;
-      a2.C = y_shared; a2.ldc = c.d; a2.ws = static_cast<float*>(ws);
+      a2.C = y_shared; a2.ldc = c.d;
       g2.grp_offset = plan->exp_offset; g2.grp_widx = plan->pos_expert; g2.ngroups = c.E;
       g2.a_rows_total = n_epd;
-      a2.w_base = c.E; a2.ngroups = c.S; a2.M = c.T; a2.a_rows_total = c.T;
+      a2.w_base = c.E; a2.ngroups = 1; a2.M = c.T; a2.a_rows_total = c.T;
       rc = launch_skinny(g2, &a2, false, n_epd, s);
       if (rc) return rc;
-      const size_t quads = (size_t)c.T * c.d / 4;
-      hipLaunchKernelGGL(splitk_reduce_bf16, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
-                         static_cast<const float*>(ws), c.S, c.T, c.d, static_cast<__bf16*>(y_shared), c.d, 0);
-      OCC_LAUNCH_CHECK("splitk_reduce_bf16");
     }
     return OCCULT_OK;
   }

@@ -9,7 +9,6 @@ struct GemmArgs {
   const void* A;            // activation rows, K-contiguous
   int lda;                  // elements between A rows
   const int32_t* a_rows;    // [rows] source row of each logical row, or NULL (identity)
-  int a_group_cols;         // group g reads its A rows from column g * a_group_cols on (weight-streaming kernel only)
   const void* B;            // weights [group][N][kseg]
   const void* B2;           // second weight matrix (up projection) when SWIGLU, same layout
   const void* Bp;           // the same weights in the weight-streaming kernel's own order (occult_pack_weights),
@@ -34,8 +33,7 @@ struct GemmArgs {
   int plain_map;            // small-tile kernel: workgroup id = m-tile * n_tiles + n-tile (tiny grids)
   int ksplit;               // small-tile kernel, one group, no SWIGLU: blockIdx.y takes K tiles
                             // [y*nk/ksplit, (y+1)*nk/ksplit) and writes f32 sums to ws; 0 or 1 = off
-  float* ws;                // [ksplit][M][N] partial sums; weight-streaming kernel (uniform groups, no SWIGLU): when
-                            // not NULL group g writes its f32 product to ws[g][M][N] instead of C
+  float* ws;                // [ksplit][M][N] partial sums
   int N;                    // output columns (for SWIGLU: columns of h)
   int K;
 };
