@@ -277,8 +277,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs a) {
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel for groups of a few rows (decode-shaped layers), where the work is streaming
 // every active expert's weights from HBM once.  No LDS tiles, no barriers in the K loop: each wave
-// owns 32 output columns x up to 16*MT tokens over the whole K and loads both operands straight
-// into MFMA fragment registers.  v_mfma_f32_16x16x32_bf16 takes 8 consecutive K elements per lane
+// owns 32 output columns x up to 16*MT tokens over the whole K (or a quarter of it: KSPLIT below)
+// and loads both operands straight into MFMA fragment registers.  v_mfma_f32_16x16x32_bf16 takes 8 consecutive K elements per lane
 // and 4 lanes per row, so one load instruction reads 16 rows x one whole 64-byte sector.  Weights
 // are the row operand: a lane ends up with 4 consecutive output columns of one token (8-byte
 // stores).  The operands of the next K step (4 or 8 KiB of weights per wave) are in flight while
@@ -295,9 +295,9 @@ namespace skinny {
 constexpr int BN_OUT = 32;
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-// KSPLIT (first problem; the second always): the four waves of a workgroup take the four quarters of K of ONE column block and add their sums through
-// LDS (quarters in ascending order, so the result is reproducible) instead of taking four column blocks over the
-// whole K.  A wave's stream is then a quarter as long and there are four times as many workgroups, which the
+// KSPLIT (for the first problem; the second always does): the four waves of a workgroup take the four quarters of K
+// of ONE column block and add their sums through LDS (quarters in ascending order, so the result is reproducible)
+// instead of taking four column blocks over the whole K.  A wave's stream is then a quarter as long and there are four times as many workgroups, which the
 // hardware hands to whichever CU has room: with whole-K waves a layer's 2000-4000 waves fill the chip's 1024 SIMDs
 // two to four deep, all finish together, and a last partly filled layer of waves costs a whole stream's time.
 template <bool SWIGLU, int MT, bool PACKED, bool KSPLIT>   // MT token blocks of 16 per m-tile; PACKED: weights from a.Bp
@@ -320,7 +320,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
   } else {
     // Uniform groups of P m-tiles each: the P workgroups that stream the same weights (one per m-tile) get ids
     // 8 apart, so they run on the same XCD (workgroups go to the 8 XCDs round-robin) at about the same time and
-    // all but the first of them find the weights in that XCD's L2.  unit = (group, four column blocks).
+    // all but the first of them find the weights in that XCD's L2.  unit = (group, column block).
     // (Measured against the four waves of one workgroup taking the m-tiles of one column block, which shares
     // the weights inside a CU: that was slower from 64 tokens on.)
     const int b = (int)blockIdx.x - a_blocks;
