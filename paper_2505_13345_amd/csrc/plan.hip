@@ -3,17 +3,18 @@
 //
 // The printed builders are sequential counters: BRIM_0 numbers (device, token) pairs
 // device-major / token-ascending, BRIM_1 numbers (local expert, SFD row) pairs expert-major /
-// row-ascending.  Both are stable ranks, so they are computed here without atomics:
-//   pass 1  plan_count : one token per thread; per block of 256 tokens and device, how many of
-//                        the tokens touch the device and each of its placement positions (wave
-//                        ballots + popcounts, LDS);
+// row-ascending.  Both are stable ranks, so they are computed here without float atomics and in a
+// fixed order:
+//   pass 1  plan_count : one token per thread; per block of 256 tokens, the set of its tokens that
+//                        touch each device and each placement position (bit-or into LDS), and the
+//                        sets' sizes;
 //   pass 2  plan_scan  : one block turns the [blocks][D+E] counts into exclusive bases
 //                        (column scan over blocks, then a scan over devices / positions);
-//   pass 3  plan_fill  : every block repeats its ballots and writes the rank-addressed tables;
-//                        one block per (256 tokens, device), so that D times more blocks share
-//                        the (device, slot) loop.
-// Inside a block the order is wave-major then lane = token-ascending, which is the order the
-// sequential counters would visit.  Every table is therefore bit-reproducible.
+//   pass 3  plan_fill  : every block rebuilds its sets; a token's rank in a column is the block's
+//                        base plus the number of set bits below its own, and every token writes
+//                        its own entries of the rank-addressed tables.
+// Ranks are token-ascending, which is the order the sequential counters would visit: every table
+// is bit-reproducible.  A batch of one block (T <= 256) runs the three passes in one launch.
 #include "common.h"
 
 #include <mutex>
@@ -21,71 +22,121 @@
 namespace occult {
 
 constexpr int kTPB = kPlanTokensPerBlock;   // 256 threads = 4 waves, one token per thread
-constexpr int kWavesPerBlock = kTPB / 64;
 constexpr int kMaxCols = OCCULT_MAX_D + OCCULT_MAX_E;
 
-struct TokenBits {
-  unsigned long long dev;      // bit j: token has an expert on device j
-  unsigned long long pos[4];   // bit P: token has the expert at placement position P
+// Per block of 256 tokens every column (device j: column j; placement position P: column D + P) gets a 256-bit set
+// of the block's tokens that touch it, built in LDS with bit-or (order-free, so deterministic).  A column's count is
+// the number of set bits, a token's rank inside its block the number of set bits below its own: the same
+// token-ascending ranks the sequential counters give, without a wave vote per column.
+typedef unsigned long long TokenSet[4];
+
+__device__ __forceinline__ int bits_below(const unsigned long long* col, int tl) {
+  const int tw = tl >> 6;
+  const unsigned long long part = (1ull << (tl & 63)) - 1ull;
+  int n = 0;
+#pragma unroll
+  for (int wd = 0; wd < 4; ++wd) n += __popcll(col[wd] & (wd < tw ? ~0ull : (wd == tw ? part : 0ull)));
+  return n;
+}
+
+// A token's selected placement positions (a position named by several slots counts once, with the gate of the
+// last), their devices and gates; -1 / 0 in unused slots.  k <= KMAX.
+template <int KMAX>
+struct TokenSlots {
+  int pos[KMAX], dev[KMAX];
+  float gate[KMAX];
+  unsigned long long devmask;
 };
 
-__device__ __forceinline__ TokenBits token_bits(const int32_t* __restrict__ ids, int t, int T, int k,
-                                                int G, const int* s_pos) {
-  TokenBits b;
-  b.dev = 0;
-  b.pos[0] = b.pos[1] = b.pos[2] = b.pos[3] = 0;
-  if (t < T) {
-    for (int s = 0; s < k; ++s) {
-      const int P = s_pos[ids[(size_t)t * k + s]];
-      b.dev |= 1ull << (P / G);
-      const unsigned long long bit = 1ull << (P & 63);
-      const int word = P >> 6;
-      b.pos[0] |= (word == 0) ? bit : 0ull;
-      b.pos[1] |= (word == 1) ? bit : 0ull;
-      b.pos[2] |= (word == 2) ? bit : 0ull;
-      b.pos[3] |= (word == 3) ? bit : 0ull;
-    }
-  }
-  return b;
-}
-
-__device__ __forceinline__ bool has_pos(const TokenBits& b, int P) {
-  const int word = P >> 6;
-  const unsigned long long m =
-      word == 0 ? b.pos[0] : (word == 1 ? b.pos[1] : (word == 2 ? b.pos[2] : b.pos[3]));
-  return (m >> (P & 63)) & 1ull;
-}
-
-__global__ __launch_bounds__(kTPB) void plan_count(const int32_t* __restrict__ ids, int T, int k, int E,
-                                                   int D, int G, const int32_t* __restrict__ expert_pos,
-                                                   uint64_t* __restrict__ tok_devmask,
-                                                   int32_t* __restrict__ blk_cnt) {
-  __shared__ int s_pos[OCCULT_MAX_E];
-  __shared__ int s_cnt[kWavesPerBlock][kMaxCols];
-  for (int e = threadIdx.x; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
-  __syncthreads();
-  const int t = blockIdx.x * kTPB + threadIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
-  const int j = blockIdx.y;   // this block counts device j and its G positions
-  if (j == 0 && t < T) tok_devmask[t] = b.dev;
-  {
-    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
-    if (lane == 0) s_cnt[wave][j] = __popcll(m);
-    for (int sl = 0; sl < G; ++sl) {
-      const unsigned long long mp = __ballot(has_pos(b, j * G + sl));
-      if (lane == 0) s_cnt[wave][D + j * G + sl] = __popcll(mp);
-    }
-  }
-  __syncthreads();
-  const int C = D + E;
-  for (int i = threadIdx.x; i <= G; i += kTPB) {
-    const int c = i == 0 ? j : D + j * G + i - 1;
-    int sum = 0;
+template <int KMAX, bool GATES>
+__device__ __forceinline__ void load_token(TokenSlots<KMAX>& ts, const int32_t* __restrict__ ids,
+                                           const float* __restrict__ w, int t, int T, int k, int G, const int* s_pos) {
 #pragma unroll
-    for (int wv = 0; wv < kWavesPerBlock; ++wv) sum += s_cnt[wv][c];
-    blk_cnt[(size_t)blockIdx.x * C + c] = sum;
+  for (int s = 0; s < KMAX; ++s) {
+    const bool live = (t < T) && (s < k);
+    ts.pos[s] = live ? s_pos[ids[(size_t)t * k + s]] : -1;
+    ts.gate[s] = (GATES && live) ? w[(size_t)t * k + s] : 0.0f;
   }
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s)
+#pragma unroll
+    for (int s2 = s + 1; s2 < KMAX; ++s2)
+      if (ts.pos[s] >= 0 && ts.pos[s2] == ts.pos[s]) ts.pos[s] = -1;
+  ts.devmask = 0;
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    ts.dev[s] = ts.pos[s] >= 0 ? ts.pos[s] / G : -1;
+    if (ts.pos[s] >= 0) ts.devmask |= 1ull << ts.dev[s];
+  }
+}
+
+// the token at bit tl of its block joins the sets of its devices and positions
+template <int KMAX>
+__device__ __forceinline__ void join_sets(TokenSet* s_set, int D, int tl, const TokenSlots<KMAX>& ts) {
+  const unsigned long long mybit = 1ull << (tl & 63);
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s)
+    if (ts.pos[s] >= 0) {
+      atomicOr(&s_set[D + ts.pos[s]][tl >> 6], mybit);
+      atomicOr(&s_set[ts.dev[s]][tl >> 6], mybit);
+    }
+}
+
+// Token t (bit tl of its block) writes its own entries of every table: base[c] = rank of its block's first token in
+// column c.  The merge list of an SFD row is position-ascending.
+template <int KMAX>
+__device__ __forceinline__ void fill_token(const TokenSlots<KMAX>& ts, int t, int tl, int D, int M1, const TokenSet* s_set,
+                                           const int* base, int32_t* __restrict__ tok_sfd_row,
+                                           int32_t* __restrict__ sfd_token, int32_t* __restrict__ epd_sfd_row,
+                                           float* __restrict__ epd_gate, int32_t* __restrict__ sfd_epd_rows) {
+  for (int j = 0; j < D; ++j) {
+    const bool on = (ts.devmask >> j) & 1ull;
+    const int r = on ? base[j] + bits_below(s_set[j], tl) : -1;
+    tok_sfd_row[(size_t)t * D + j] = r;
+    if (on) {
+      sfd_token[r] = t;
+      int filled = 0;
+#pragma unroll
+      for (int s = 0; s < KMAX; ++s) filled += ts.dev[s] == j ? 1 : 0;
+      for (int i = filled; i < M1; ++i) sfd_epd_rows[(size_t)r * M1 + i] = -1;
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    const int P = ts.pos[s];
+    if (P < 0) continue;
+    const int j = ts.dev[s];
+    const int r = base[j] + bits_below(s_set[j], tl);
+    const int q = base[D + P] + bits_below(s_set[D + P], tl);
+    int before = 0;   // this token's other positions on the same device below P
+#pragma unroll
+    for (int s2 = 0; s2 < KMAX; ++s2) before += (ts.dev[s2] == j && ts.pos[s2] < P) ? 1 : 0;
+    epd_sfd_row[q] = r;
+    epd_gate[q] = ts.gate[s];
+    sfd_epd_rows[(size_t)r * M1 + before] = q;
+  }
+}
+
+// pass 1: per block of 256 tokens, how many of them touch each device and each placement position
+template <int KMAX>
+__global__ __launch_bounds__(kTPB) void plan_count(const int32_t* __restrict__ ids, int T, int k, int E, int D, int G,
+                                                   const int32_t* __restrict__ expert_pos,
+                                                   uint64_t* __restrict__ tok_devmask, int32_t* __restrict__ blk_cnt) {
+  static_assert(kTPB == 256, "token sets are four 64-bit words");
+  __shared__ int s_pos[OCCULT_MAX_E];
+  __shared__ TokenSet s_set[kMaxCols];
+  const int tl = threadIdx.x, t = blockIdx.x * kTPB + tl, C = D + E;
+  for (int e = tl; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
+  for (int i = tl; i < C * 4; i += kTPB) (&s_set[0][0])[i] = 0ull;
+  __syncthreads();
+  TokenSlots<KMAX> ts;
+  load_token<KMAX, false>(ts, ids, nullptr, t, T, k, G, s_pos);
+  join_sets<KMAX>(s_set, D, tl, ts);
+  if (t < T) tok_devmask[t] = ts.devmask;
+  __syncthreads();
+  for (int c = tl; c < C; c += kTPB)
+    blk_cnt[(size_t)blockIdx.x * C + c] =
+        __popcll(s_set[c][0]) + __popcll(s_set[c][1]) + __popcll(s_set[c][2]) + __popcll(s_set[c][3]);
 }
 
 // One block of 1024 threads.  Thread (part, c) owns rows [part*rpp, (part+1)*rpp) of column c.
@@ -166,7 +217,9 @@ __global__ __launch_bounds__(kScanThreads) void plan_scan(
   }
 }
 
-template <int KMAX>   // k <= KMAX: a token's positions and gates stay in registers
+// pass 3: every block rebuilds its token sets and its tokens write the rank-addressed tables; blk_base holds, per
+// block and column, the rank of the block's first token (pass 2)
+template <int KMAX>
 __global__ __launch_bounds__(kTPB) void plan_fill(
     const int32_t* __restrict__ ids, const float* __restrict__ w, int T, int k, int E, int D, int G,
     int M1, const int32_t* __restrict__ expert_pos, const int32_t* __restrict__ blk_base,
@@ -174,96 +227,22 @@ __global__ __launch_bounds__(kTPB) void plan_fill(
     int32_t* __restrict__ epd_sfd_row, float* __restrict__ epd_gate,
     int32_t* __restrict__ sfd_epd_rows) {
   __shared__ int s_pos[OCCULT_MAX_E];
-  __shared__ int s_cnt[kWavesPerBlock][kMaxCols];
-  for (int e = threadIdx.x; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
+  __shared__ TokenSet s_set[kMaxCols];
+  __shared__ int s_base[kMaxCols];
+  const int tl = threadIdx.x, t = blockIdx.x * kTPB + tl, C = D + E;
+  for (int e = tl; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
+  for (int i = tl; i < C * 4; i += kTPB) (&s_set[0][0])[i] = 0ull;
+  for (int c = tl; c < C; c += kTPB) s_base[c] = blk_base[(size_t)blockIdx.x * C + c];
   __syncthreads();
-  const int t = blockIdx.x * kTPB + threadIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const TokenBits b = token_bits(ids, t, T, k, G, s_pos);
-  // the token's selected positions and gates, kept in registers: looking a hit up by comparing
-  // against them costs a few ALU operations, re-reading ids / w per hit would cost a dependent
-  // memory round trip inside the rank loop
-  int tpos[KMAX];
-  float tgate[KMAX];
-#pragma unroll
-  for (int s = 0; s < KMAX; ++s) {
-    const bool live = (t < T) && (s < k);
-    tpos[s] = live ? s_pos[ids[(size_t)t * k + s]] : -1;
-    tgate[s] = live ? w[(size_t)t * k + s] : 0.0f;
-  }
-  // this block's device and its columns: the device itself and its G placement positions
-  const int j = blockIdx.y;
-  {
-    const unsigned long long m = __ballot((b.dev >> j) & 1ull);
-    if (lane == 0) s_cnt[wave][j] = __popcll(m);
-    for (int sl = 0; sl < G; ++sl) {
-      const unsigned long long mp = __ballot(has_pos(b, j * G + sl));
-      if (lane == 0) s_cnt[wave][D + j * G + sl] = __popcll(mp);
-    }
-  }
+  TokenSlots<KMAX> ts;
+  load_token<KMAX, true>(ts, ids, w, t, T, k, G, s_pos);
+  join_sets<KMAX>(s_set, D, tl, ts);
   __syncthreads();
-
-  // per-wave counts -> first rank of each wave in each column: block base + waves before it
-  const int C = D + E;
-  for (int i = threadIdx.x; i <= G; i += kTPB) {
-    const int c = i == 0 ? j : D + j * G + i - 1;
-    int run = blk_base[(size_t)blockIdx.x * C + c];
-#pragma unroll
-    for (int wv = 0; wv < kWavesPerBlock; ++wv) {
-      const int n = s_cnt[wv][c];
-      s_cnt[wv][c] = run;
-      run += n;
-    }
-  }
-  __syncthreads();
-  const int* first = s_cnt[wave];
-  const unsigned long long lt = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-
-  {
-    const bool on = (b.dev >> j) & 1ull;
-    const unsigned long long m = __ballot(on);
-    const int r = on ? first[j] + __popcll(m & lt) : -1;
-    if (t < T) tok_sfd_row[(size_t)t * D + j] = r;
-    if (on) sfd_token[r] = t;
-
-    int filled = 0;   // merge-list entries of SFD row r written so far
-    for (int sl = 0; sl < G; ++sl) {
-      const int P = j * G + sl;
-      const bool hit = has_pos(b, P);
-      const unsigned long long me = __ballot(hit);
-      if (me == 0ull) continue;   // wave-uniform
-      if (hit) {
-        const int q = first[D + P] + __popcll(me & lt);
-        float gate = 0.0f;
-#pragma unroll
-        for (int s = 0; s < KMAX; ++s) gate = (tpos[s] == P) ? tgate[s] : gate;
-        epd_sfd_row[q] = r;
-        epd_gate[q] = gate;
-        sfd_epd_rows[(size_t)r * M1 + filled] = q;
-        ++filled;
-      }
-    }
-    if (on)
-      for (int i = filled; i < M1; ++i) sfd_epd_rows[(size_t)r * M1 + i] = -1;
-  }
+  if (t < T) fill_token<KMAX>(ts, t, tl, D, M1, s_set, s_base, tok_sfd_row, sfd_token, epd_sfd_row, epd_gate, sfd_epd_rows);
 }
 
-// A batch of at most one block of tokens (T <= 256: decode steps): the whole plan in one launch of one block, and
-// without the per-column ballot loops of the three kernels above (D + E wave votes each for counting and for filling,
-// most of a small batch's planning time).  Each column (device or placement position) gets a 256-bit set of the tokens
-// that touch it, built with LDS bit-or (order-free, so deterministic); a token's rank in a column is then the number
-// of set bits below its own, the column's count the number of set bits, and every token writes its own table entries
-// from those.  The ranks are the same token-ascending ranks the sequential counters give: tables bit-identical to
-// the three-kernel path.
-__device__ __forceinline__ int bits_below(const unsigned long long* col, int t) {
-  const int tw = t >> 6;
-  const unsigned long long part = (1ull << (t & 63)) - 1ull;
-  int n = 0;
-#pragma unroll
-  for (int wd = 0; wd < 4; ++wd) n += __popcll(col[wd] & (wd < tw ? ~0ull : (wd == tw ? part : 0ull)));
-  return n;
-}
-
+// A batch of at most one block of tokens (T <= 256: decode steps): the three passes in one launch of one block,
+// the column counts and their scans held in LDS.  Tables bit-identical to the three-kernel path.
 template <int KMAX>
 __global__ __launch_bounds__(kTPB) void plan_single(
     const int32_t* __restrict__ ids, const float* __restrict__ w, int T, int k, int E, int D, int G, int M1,
@@ -272,45 +251,19 @@ __global__ __launch_bounds__(kTPB) void plan_single(
     int32_t* __restrict__ pos_expert, uint64_t* __restrict__ counters, int32_t* __restrict__ tok_sfd_row,
     int32_t* __restrict__ sfd_token, int32_t* __restrict__ epd_sfd_row, float* __restrict__ epd_gate,
     int32_t* __restrict__ sfd_epd_rows) {
-  static_assert(kTPB == 256, "token sets are four 64-bit words");
   __shared__ int s_pos[OCCULT_MAX_E];
-  __shared__ unsigned long long s_set[kMaxCols][4];   // columns: devices 0..D-1, then positions D..D+E-1
-  __shared__ int s_n[kMaxCols];                       // column counts
-  __shared__ int s_start[kMaxCols];                   // exclusive scans: devices, then positions
+  __shared__ TokenSet s_set[kMaxCols];
+  __shared__ int s_n[kMaxCols];       // column counts
+  __shared__ int s_start[kMaxCols];   // exclusive scans: devices, then positions
   const int t = threadIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int C = D + E;
   for (int e = t; e < E; e += kTPB) s_pos[e] = expert_pos ? expert_pos[e] : e;
   for (int i = t; i < C * 4; i += kTPB) (&s_set[0][0])[i] = 0ull;
   __syncthreads();
-
-  // this token's positions and gates; a position named by several slots counts once, with the gate of the last
-  int tpos[KMAX];
-  float tgate[KMAX];
-  unsigned long long dev = 0;
-#pragma unroll
-  for (int s = 0; s < KMAX; ++s) {
-    const bool live = (t < T) && (s < k);
-    tpos[s] = live ? s_pos[ids[(size_t)t * k + s]] : -1;
-    tgate[s] = live ? w[(size_t)t * k + s] : 0.0f;
-  }
-#pragma unroll
-  for (int s = 0; s < KMAX; ++s)
-#pragma unroll
-    for (int s2 = s + 1; s2 < KMAX; ++s2)
-      if (tpos[s] >= 0 && tpos[s2] == tpos[s]) tpos[s] = -1;
-  int tdev[KMAX];   // device of each surviving position
-#pragma unroll
-  for (int s = 0; s < KMAX; ++s) tdev[s] = tpos[s] >= 0 ? tpos[s] / G : -1;
-  const unsigned long long mybit = 1ull << (t & 63);
-#pragma unroll
-  for (int s = 0; s < KMAX; ++s)
-    if (tpos[s] >= 0) {
-      const int j = tdev[s];
-      dev |= 1ull << j;
-      atomicOr(&s_set[D + tpos[s]][t >> 6], mybit);
-      atomicOr(&s_set[j][t >> 6], mybit);
-    }
-  if (t < T) tok_devmask[t] = dev;
+  TokenSlots<KMAX> ts;
+  load_token<KMAX, true>(ts, ids, w, t, T, k, G, s_pos);
+  join_sets<KMAX>(s_set, D, t, ts);
+  if (t < T) tok_devmask[t] = ts.devmask;
   __syncthreads();
 
   for (int c = t; c < C; c += kTPB)
@@ -359,34 +312,7 @@ __global__ __launch_bounds__(kTPB) void plan_single(
     for (int e = t - 128; e < E; e += kTPB - 128) pos_expert[s_pos[e]] = e;
   }
   __syncthreads();
-
-  if (t >= T) return;
-  for (int j = 0; j < D; ++j) {
-    const bool on = (dev >> j) & 1ull;
-    const int r = on ? s_start[j] + bits_below(s_set[j], t) : -1;
-    tok_sfd_row[(size_t)t * D + j] = r;
-    if (on) {
-      sfd_token[r] = t;
-      int filled = 0;
-#pragma unroll
-      for (int s = 0; s < KMAX; ++s) filled += tdev[s] == j ? 1 : 0;
-      for (int i = filled; i < M1; ++i) sfd_epd_rows[(size_t)r * M1 + i] = -1;
-    }
-  }
-#pragma unroll
-  for (int s = 0; s < KMAX; ++s) {
-    const int P = tpos[s];
-    if (P < 0) continue;
-    const int j = tdev[s];
-    const int r = s_start[j] + bits_below(s_set[j], t);
-    const int q = s_start[D + P] + bits_below(s_set[D + P], t);
-    int before = 0;   // this token's other positions on the same device below P: the merge list is position-ascending
-#pragma unroll
-    for (int s2 = 0; s2 < KMAX; ++s2) before += (tdev[s2] == j && tpos[s2] < P) ? 1 : 0;
-    epd_sfd_row[q] = r;
-    epd_gate[q] = tgate[s];
-    sfd_epd_rows[(size_t)r * M1 + before] = q;
-  }
+  if (t < T) fill_token<KMAX>(ts, t, t, D, M1, s_set, s_start, tok_sfd_row, sfd_token, epd_sfd_row, epd_gate, sfd_epd_rows);
 }
 
 size_t plan_workspace_bytes(const occult_cfg_t& c);
@@ -411,8 +337,13 @@ static int launch_plan(const occult_cfg_t& c, const int32_t* ids, const float* w
     return OCCULT_OK;
   }
   if (nblk > 0) {
-    hipLaunchKernelGGL(plan_count, dim3(nblk, c.D), dim3(kTPB), 0, s, ids, c.T, c.k, c.E, c.D, G, c.expert_pos,
-                       p.tok_devmask, blk);
+#define OCC_PLAN_COUNT(KM)                                                                               \
+  hipLaunchKernelGGL(plan_count<KM>, dim3(nblk), dim3(kTPB), 0, s, ids, c.T, c.k, c.E, c.D, G, c.expert_pos, \
+                     p.tok_devmask, blk)
+    if (c.k <= 8) OCC_PLAN_COUNT(8);
+    else if (c.k <= 16) OCC_PLAN_COUNT(16);
+    else OCC_PLAN_COUNT(32);
+#undef OCC_PLAN_COUNT
     OCC_LAUNCH_CHECK("plan_count");
   }
   // with T == 0 the scan still writes zero counts and offsets
@@ -422,7 +353,7 @@ static int launch_plan(const occult_cfg_t& c, const int32_t* ids, const float* w
   OCC_LAUNCH_CHECK("plan_scan");
   if (nblk > 0) {
 #define OCC_PLAN_FILL(KM)                                                                              \
-  hipLaunchKernelGGL(plan_fill<KM>, dim3(nblk, c.D), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G,    \
+  hipLaunchKernelGGL(plan_fill<KM>, dim3(nblk), dim3(kTPB), 0, s, ids, w, c.T, c.k, c.E, c.D, G,         \
                      merge_width(c), c.expert_pos, blk, p.tok_sfd_row, p.sfd_token, p.epd_sfd_row,       \
                      p.epd_gate, p.sfd_epd_rows)
     if (c.k <= 8) OCC_PLAN_FILL(8);
