@@ -360,17 +360,29 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
   const char* wp = PACKED ? static_cast<const char*>(a.Bp) + widx * a.bp_group_stride + cb * unit_bytes
                           : nullptr;   // scalar; a lane reads at lane * 16 from it
   const unsigned lane16 = lane * 16;
-  // token rows: a scalar base plus a 32-bit byte offset per lane (host: A < 4 GiB)
+  // token rows: a scalar base plus a 32-bit byte offset per lane (host: A < 4 GiB).  The MFMA wants lane l to hold row
+  // l % 16, K group l / 16, which would make neighbouring lanes read rows that lie a whole row pitch apart (16 cache
+  // lines looked up per 16 lanes).  The rows are loaded instead with lane l on row l / 4, K group l % 4 (four
+  // neighbouring lanes = one 64-byte sector, 4 lines per 16 lanes) and put into the MFMA's order by a lane permutation
+  // just before use (ds_bpermute: the LDS crossbar, no LDS memory).
   const char* xbase = static_cast<const char*>(a.A);
   unsigned xo[MT];
 #pragma unroll
   for (int tb = 0; tb < MT; ++tb) {
-    int lr = ti.m0 + tb * 16 + r;
+    int lr = ti.m0 + tb * 16 + (lane >> 2);
     if (lr >= ti.rows) lr = ti.rows - 1;   // tokens past the group's end repeat its last row; dropped at the end
     const int logical = ti.row_base + lr;
     const unsigned src = a.a_rows ? a.a_rows[logical] : logical;
-    xo[tb] = (src * (unsigned)a.lda) * 2u + c * 16;
+    xo[tb] = (src * (unsigned)a.lda) * 2u + (lane & 3) * 16;
   }
+  const int from_lane4 = (r * 4 + c) * 4;   // byte index of the lane that loaded what this lane multiplies
+  auto to_mfma_order = [&](const bf16x8& v) {
+    typedef int i32x4v __attribute__((ext_vector_type(4)));
+    i32x4v t = __builtin_bit_cast(i32x4v, v);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t[e] = __builtin_amdgcn_ds_bpermute(from_lane4, t[e]);
+    return __builtin_bit_cast(bf16x8, t);
+  };
 
   f32x4v acc[NW][2][MT];
 #pragma unroll
@@ -423,11 +435,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
 #pragma unroll
       for (int tb = 0; tb < MT; ++tb)
         if (tb < nblk) {
+          const bf16x8 xf = to_mfma_order(st.xf[ks][tb]);
 #pragma unroll
           for (int m = 0; m < NW; ++m)
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
-              acc[m][nb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.wf[ks][m][nb], st.xf[ks][tb], acc[m][nb][tb], 0, 0, 0);
+              acc[m][nb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.wf[ks][m][nb], xf, acc[m][nb][tb], 0, 0, 0);
         }
   };
 
