@@ -353,8 +353,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
   for (int m = 0; m < NW; ++m)
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
-      w[m][nb] = static_cast<const char*>(m == 0 ? a.B : a.B2) +
-                 ((widx * a.b_group_stride + (long long)(n0 + nb * 16 + r) * a.ldb) * 2 + c * 16);
+      w[m][nb] = static_cast<const char*>(m == 0 ? a.B : a.B2) +   // loaded like the token rows: lane l on row l / 4
+                 ((widx * a.b_group_stride + (long long)(n0 + nb * 16 + (lane >> 2)) * a.ldb) * 2 + (lane & 3) * 16);
   // packed order: this wave's unit is one contiguous stream of stages, a load instruction reads 1 KiB of it
   const long long unit_bytes = (long long)(BN_OUT * NW * 2) * a.kseg;   // one unit's stream inside one weight matrix
   const char* wp = PACKED ? static_cast<const char*>(a.Bp) + widx * a.bp_group_stride + cb * unit_bytes
@@ -431,7 +431,12 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
   };
   auto multiply = [&](const Stage& st) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 wfo[NW][2];   // the packed order is the MFMA's already
+#pragma unroll
+      for (int m = 0; m < NW; ++m)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) wfo[m][nb] = PACKED ? st.wf[ks][m][nb] : to_mfma_order(st.wf[ks][m][nb]);
 #pragma unroll
       for (int tb = 0; tb < MT; ++tb)
         if (tb < nblk) {
@@ -440,8 +445,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_bf16(const GemmArgs first, c
           for (int m = 0; m < NW; ++m)
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
-              acc[m][nb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.wf[ks][m][nb], xf, acc[m][nb][tb], 0, 0, 0);
+              acc[m][nb][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfo[m][nb], xf, acc[m][nb][tb], 0, 0, 0);
         }
+    }
   };
 
   // this wave's stages of K
