@@ -295,17 +295,30 @@ __global__ __launch_bounds__(256) void router_kernel(const __bf16* __restrict__ 
   const int r = lane & 15, c = lane >> 4;
   const int tok0 = blockIdx.x * kRouterTokens;
   const int kq = d / 4;   // host: d % 128 == 0
-  const size_t koff = ((size_t)wave * kq + c * 8) * 2;
+  // The MFMA wants lane l on row l % 16, K group l / 16; loaded that way neighbouring lanes would read rows a whole
+  // row pitch apart (16 cache lines looked up per 16 lanes).  Rows are loaded with lane l on row l / 4, K group l % 4
+  // (four neighbouring lanes = one 64-byte sector) and permuted into the MFMA's order before use (ds_bpermute: the
+  // LDS crossbar, no LDS memory).
+  const int lrow = lane >> 2;
+  const size_t koff = ((size_t)wave * kq + (lane & 3) * 8) * 2;
+  const int from_lane4 = (r * 4 + c) * 4;   // byte index of the lane that loaded what this lane multiplies
+  auto to_mfma_order = [&](const bf16x8& v) {
+    typedef int i32x4v __attribute__((ext_vector_type(4)));
+    i32x4v t = __builtin_bit_cast(i32x4v, v);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t[e] = __builtin_amdgcn_ds_bpermute(from_lane4, t[e]);
+    return __builtin_bit_cast(bf16x8, t);
+  };
   const char* xp[2];
 #pragma unroll
   for (int tb = 0; tb < 2; ++tb) {
-    const int t = min(tok0 + tb * 16 + r, T - 1);   // rows past the end repeat the last token; not written
+    const int t = min(tok0 + tb * 16 + lrow, T - 1);   // rows past the end repeat the last token; not written
     xp[tb] = reinterpret_cast<const char*>(x) + (size_t)t * d * 2 + koff;
   }
   const char* wp[EB];
 #pragma unroll
   for (int eb = 0; eb < EB; ++eb) {
-    const int e = min(eb * 16 + r, E - 1);
+    const int e = min(eb * 16 + lrow, E - 1);
     wp[eb] = reinterpret_cast<const char*>(wr) + (size_t)e * d * 2 + koff;
   }
   f32x4v acc[2][EB];
@@ -343,11 +356,16 @@ __global__ __launch_bounds__(256) void router_kernel(const __bf16* __restrict__ 
     for (int q = 0; q < XS; ++q) {
       load_w((q + WD - 1) % WD, first + q + WD - 1);
       if (first + q < nst) {
+        bf16x8 xo[2], wo[EB];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) xo[tb] = to_mfma_order(ch.xf[q][tb]);
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb) wo[eb] = to_mfma_order(wf[q % WD][eb]);
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
           for (int eb = 0; eb < EB; ++eb)
-            acc[tb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[q % WD][eb], ch.xf[q][tb], acc[tb][eb], 0, 0, 0);
+            acc[tb][eb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wo[eb], xo[tb], acc[tb][eb], 0, 0, 0);
       }
     }
   };
