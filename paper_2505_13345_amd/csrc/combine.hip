@@ -20,7 +20,10 @@ namespace occult {
 
 constexpr int kCombWaves = 4;
 
-template <bool BF16, int VPL>
+// AHEAD (needs lists_fit and a row within 64 * VPL vectors): the token's EPD rows are walked as one list in lane order
+// (= device order, then slot order) and the next row is requested before the current one is summed, so a wave has
+// two rows in flight instead of one (a third changed nothing).  The sums, their order and their roundings are those of the other path.
+template <bool BF16, int VPL, bool AHEAD>
 __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
     const void* __restrict__ epd_y, void* __restrict__ sfd_y, const void* __restrict__ y_shared,
     void* __restrict__ y, const int32_t* __restrict__ tok_sfd_row,
@@ -53,6 +56,80 @@ __global__ __launch_bounds__(kCombWaves * 64) void combine_kernel(
       }
     }
 
+    if constexpr (AHEAD) {
+      typedef typename R::Raw Raw;
+      const int my_o = lane / M1;   // lane (o, m): which of the token's devices the lane's entry belongs to
+      unsigned long long todo = __ballot(my_q >= 0);
+      const int n_rows = __popcll(todo);
+      Raw cur[VPL], nxt[VPL];
+      int e_cur = 0, e_nxt = 0;
+      auto request = [&](int e, Raw (&into)[VPL]) {
+        const int q = __builtin_amdgcn_readlane(my_q, e);
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+          const int c = lane + 64 * v;
+          if (c < row_vecs) into[v] = R::load_raw(epd_y, (size_t)q, row_vecs, c);
+        }
+      };
+      if (n_rows > 0) {
+        e_cur = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        request(e_cur, cur);
+      }
+
+      float acc[VPL][NE], part[VPL][NE];
+#pragma unroll
+      for (int v = 0; v < VPL; ++v)
+#pragma unroll
+        for (int e = 0; e < NE; ++e) acc[v][e] = part[v][e] = 0.0f;
+      for (int i = 0; i < n_rows; ++i) {
+        const bool more = i + 1 < n_rows;
+        if (more) {   // wave-uniform
+          e_nxt = __ffsll((long long)todo) - 1;
+          todo &= todo - 1;
+          request(e_nxt, nxt);
+        }
+        const float g = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, my_g), e_cur));
+        const int j = __builtin_amdgcn_readlane(my_o, e_cur);
+        const bool last_of_device = !more || __builtin_amdgcn_readlane(my_o, e_nxt) != j;
+        const int r = __builtin_amdgcn_readlane(my_row, j);
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+          const int c = lane + 64 * v;
+          if (c < row_vecs) {
+            float x[NE];
+            R::unpack(cur[v], x);
+#pragma unroll
+            for (int e = 0; e < NE; ++e) part[v][e] = fmaf(g, x[e], part[v][e]);
+            if (last_of_device) {   // wave-uniform: the return payload, then stage 2 on the rounded values
+              R::store_round(sfd_y, (size_t)r, row_vecs, c, part[v]);
+#pragma unroll
+              for (int e = 0; e < NE; ++e) {
+                acc[v][e] += part[v][e];
+                part[v][e] = 0.0f;
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) cur[v] = nxt[v];
+        e_cur = e_nxt;
+      }
+#pragma unroll
+      for (int v = 0; v < VPL; ++v) {
+        const int c = lane + 64 * v;
+        if (c < row_vecs) {
+          if (y_shared) {
+            float sh[NE];
+            R::load(y_shared, (size_t)t, row_vecs, c, sh);
+#pragma unroll
+            for (int e = 0; e < NE; ++e) acc[v][e] += sh[e];
+          }
+          R::store_round(y, (size_t)t, row_vecs, c, acc[v]);
+        }
+      }
+      continue;
+    }
     // rows longer than 64 * VPL vectors are done in column chunks; the index lists stay in registers
     for (int cbase = 0; cbase < row_vecs; cbase += 64 * VPL) {
     float acc[VPL][NE];
@@ -138,9 +215,16 @@ static int launch_combine(const occult_cfg_t& c, const occult_plan_t* plan, cons
   const dim3 grid((c.T + kCombWaves - 1) / kCombWaves), block(kCombWaves * 64);
   const int M1 = merge_width(c);
   const int lists_fit = min_i(c.k, c.D) * M1 <= 64 ? 1 : 0;
-#define OCC_COMB(B, N)                                                                             \
-  hipLaunchKernelGGL((combine_kernel<B, N>), grid, block, 0, s, epd, sfd, shared, out,             \
-                     plan->tok_sfd_row, plan->sfd_epd_rows, gates, c.T, c.D, M1, row_vecs, lists_fit)
+  const bool ahead = lists_fit && vpl <= 8;
+#define OCC_COMB(B, N)                                                                                     \
+  do {                                                                                                     \
+    if (ahead)                                                                                             \
+      hipLaunchKernelGGL((combine_kernel<B, N, true>), grid, block, 0, s, epd, sfd, shared, out,           \
+                         plan->tok_sfd_row, plan->sfd_epd_rows, gates, c.T, c.D, M1, row_vecs, lists_fit); \
+    else                                                                                                   \
+      hipLaunchKernelGGL((combine_kernel<B, N, false>), grid, block, 0, s, epd, sfd, shared, out,          \
+                         plan->tok_sfd_row, plan->sfd_epd_rows, gates, c.T, c.D, M1, row_vecs, lists_fit); \
+  } while (0)
   if (c.dtype == OCCULT_BF16) {
     if (vpl <= 1) OCC_COMB(true, 1);
     else if (vpl <= 2) OCC_COMB(true, 2);

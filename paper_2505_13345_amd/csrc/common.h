@@ -72,12 +72,18 @@ struct Row;
 template <>
 struct Row<true> {
   static constexpr int kElems = 8;
-  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
-    const u32x4 v = __builtin_nontemporal_load(static_cast<const u32x4*>(base) + row * row_vecs + c);
+  typedef u32x4 Raw;   // a vector as loaded
+  __device__ static Raw load_raw(const void* base, size_t row, int row_vecs, int c) {
+    return __builtin_nontemporal_load(static_cast<const u32x4*>(base) + row * row_vecs + c);
+  }
+  __device__ static void unpack(const Raw& v, float* out) {
     out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x);
     out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
     out[4] = bf16_lo(v.z); out[5] = bf16_hi(v.z);
     out[6] = bf16_lo(v.w); out[7] = bf16_hi(v.w);
+  }
+  __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
+    unpack(load_raw(base, row, row_vecs, c), out);
   }
   // stores the rounded values and returns them in `vals`
   __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
@@ -98,9 +104,13 @@ struct Row<true> {
 template <>
 struct Row<false> {
   static constexpr int kElems = 4;
+  typedef f32x4 Raw;
+  __device__ static Raw load_raw(const void* base, size_t row, int row_vecs, int c) {
+    return __builtin_nontemporal_load(static_cast<const f32x4*>(base) + row * row_vecs + c);
+  }
+  __device__ static void unpack(const Raw& v, float* out) { out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w; }
   __device__ static void load(const void* base, size_t row, int row_vecs, int c, float* out) {
-    const f32x4 v = __builtin_nontemporal_load(static_cast<const f32x4*>(base) + row * row_vecs + c);
-    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    unpack(load_raw(base, row, row_vecs, c), out);
   }
   __device__ static void store_round(void* base, size_t row, int row_vecs, int c, float* vals) {
     f32x4 v;
