@@ -293,7 +293,11 @@ def test_shared_down_projection_split_over_k_matches_unsplit():
 
 @pytest.mark.parametrize("T,S,k,E,d,f,packed", [(128, 4, 4, 60, 512, 320, False), (45, 2, 2, 16, 256, 192, True),
                                                  (1, 1, 2, 8, 128, 64, False), (33, 3, 4, 32, 256, 128, True),
-                                                 (97, 1, 6, 64, 128, 256, False)])
+                                                 (97, 1, 6, 64, 128, 256, False),
+                                                 # one K stage for the gate/up product, two for the shared down
+                                                 # projection: some waves of a K-splitting workgroup have no stage
+                                                 (20, 2, 2, 8, 64, 64, False), (20, 2, 2, 8, 64, 64, True),
+                                                 (128, 3, 2, 16, 192, 64, True)])
 def test_small_batch_shared_experts_ride_in_the_routed_launches(T, S, k, E, d, f, packed):
     """Small batches: the shared experts' two products run inside the routed experts' weight-streaming launches (the
     down projection as one product whose K walks the S matrices, its four K quarters added in order).  h_shared and
