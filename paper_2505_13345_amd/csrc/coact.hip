@@ -28,16 +28,25 @@ __global__ __launch_bounds__(kCoactThreads) void coact_lds_kernel(const int32_t*
   extern __shared__ int s_c[];   // [E*E]
   for (int i = threadIdx.x; i < E * E; i += kCoactThreads) s_c[i] = 0;
   __syncthreads();
+  // C is symmetric: only the cells on and above the diagonal are counted in LDS (the LDS atomics are what this kernel
+  // spends its time on), the flush mirrors them.  A pair of slots naming the same expert adds 2 to its diagonal cell,
+  // as the two ordered pairs would.
   for (int t = blockIdx.x * kCoactThreads + threadIdx.x; t < T; t += gridDim.x * kCoactThreads) {
     const int32_t* row = ids + (size_t)t * k;
     for (int a = 0; a < k; ++a) {
       const int ea = row[a];
-      for (int b = 0; b < k; ++b) atomicAdd(&s_c[ea * E + row[b]], 1);
+      atomicAdd(&s_c[ea * E + ea], 1);
+      for (int b = a + 1; b < k; ++b) {
+        const int eb = row[b];
+        const int lo = min(ea, eb), hi = max(ea, eb);
+        atomicAdd(&s_c[lo * E + hi], lo == hi ? 2 : 1);
+      }
     }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < E * E; i += kCoactThreads) {
-    const int v = s_c[i];
+    const int r = i / E, c = i - r * E;
+    const int v = r <= c ? s_c[i] : s_c[c * E + r];
     if (OVERWRITE) C[i] = v;
     else if (v) atomicAdd(&C[i], v);
   }
