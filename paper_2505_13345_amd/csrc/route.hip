@@ -261,9 +261,11 @@ __global__ __launch_bounds__(kRouteWavesPerBlock * 64) void route_kernel(
     const int32_t* __restrict__ expert_pos, int n_d, int prune_mode, int renorm,
     const int32_t* __restrict__ sim_table, int32_t* __restrict__ ids, float* __restrict__ w) {
   __shared__ int s_dev[OCCULT_MAX_E];
-  for (int e = threadIdx.x; e < E; e += blockDim.x)
-    s_dev[e] = (expert_pos ? expert_pos[e] : e) / G;
-  __syncthreads();
+  if (n_d > 0) {   // uniform; only pruning asks which device an expert is on
+    for (int e = threadIdx.x; e < E; e += blockDim.x)
+      s_dev[e] = (expert_pos ? expert_pos[e] : e) / G;
+    __syncthreads();
+  }
 
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * kRouteWavesPerBlock + (threadIdx.x >> 6);
