@@ -61,25 +61,35 @@ constexpr int kRowMirror = 0x140;
 constexpr int kRowBcast15 = 0x142;     // lane 15 of each row into the next row (rows 1 and 3 take it)
 constexpr int kRowBcast31 = 0x143;     // lane 31 into rows 2 and 3
 
+// (value, index) as one 64-bit key whose unsigned order is "larger value first, equal values -> lower index":
+// the value's bits made monotone (negative floats inverted, positive ones offset) in the high word, the
+// complemented index in the low word.  One 64-bit compare per step instead of three compares.
+__device__ __forceinline__ unsigned long long argmax_key(float v, int i) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const unsigned ord = u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+  return ((unsigned long long)ord << 32) | (unsigned)(~i);
+}
+
 template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ void argmax_step(float& v, int& i) {
-  const float ov = dpp_f<CTRL, ROW_MASK>(v, v);
-  const int oi = dpp_i<CTRL, ROW_MASK>(i, i);
-  const bool take = (ov > v) || (ov == v && oi < i);
-  v = take ? ov : v;
-  i = take ? oi : i;
+__device__ __forceinline__ void argmax_step(unsigned long long& key) {
+  const int lo = dpp_i<CTRL, ROW_MASK>((int)(unsigned)key, (int)(unsigned)key);
+  const int hi = dpp_i<CTRL, ROW_MASK>((int)(unsigned)(key >> 32), (int)(unsigned)(key >> 32));
+  const unsigned long long other = ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+  key = other > key ? other : key;
 }
 
 // larger value first, equal values -> lower index; result in every lane
 __device__ __forceinline__ void wave_argmax(float& v, int& i) {
-  argmax_step<kQuadSwap1, 0xF>(v, i);
-  argmax_step<kQuadSwap2, 0xF>(v, i);
-  argmax_step<kRowHalfMirror, 0xF>(v, i);
-  argmax_step<kRowMirror, 0xF>(v, i);
-  argmax_step<kRowBcast15, 0xA>(v, i);
-  argmax_step<kRowBcast31, 0xC>(v, i);
-  v = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-  i = __builtin_amdgcn_readlane(i, 63);
+  unsigned long long key = argmax_key(v, i);
+  argmax_step<kQuadSwap1, 0xF>(key);
+  argmax_step<kQuadSwap2, 0xF>(key);
+  argmax_step<kRowHalfMirror, 0xF>(key);
+  argmax_step<kRowMirror, 0xF>(key);
+  argmax_step<kRowBcast15, 0xA>(key);
+  argmax_step<kRowBcast31, 0xC>(key);
+  const unsigned ord = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(key >> 32), 63);
+  i = ~__builtin_amdgcn_readlane((int)(unsigned)key, 63);
+  v = __builtin_bit_cast(float, ord ^ ((ord >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
